@@ -1,0 +1,396 @@
+"""CPU oracle for end-to-end fault-tolerant attention (EFTA, unified verification).
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, float64 statement of what
+the GPU library must compute.  Only tests, the smoke check and the benchmark's
+``cpu_baseline`` leg may import it; the product path never does.  It shares no
+code with the HIP kernels.
+
+Two results are defined here.
+
+``attention_clean``
+    softmax(scale * Q K^T + mask) V by the definition (two passes, global row
+    maximum).  The tiled method reaches exactly this when no fault occurs
+    (Section 2.1, eq. (2)-(8)), so this is the reference for fault-free output.
+
+``efta_rows``
+    Algorithm 1 ("EFTA with unified verification", Section 3.4) taken step by
+    step in float64 for a set of query rows of one (batch, head): tensor-checksum
+    encoding (eq. (13), (14)), GEMM I with its two checksum products (eq. (15),
+    (16)), running max, exp, the unified product-form check of GEMM I + subtract
+    + exp (Section 3.4, case 2), checksum correction / exp recomputation,
+    row-sum, GEMM II with rescale and its two checksum products, the range
+    check of the row-sum with substitution of the lower bound (case 3 and the
+    "optimized" paragraph of Section 3.4), normalisation and the final sum-form
+    check of GEMM II + rescale + normalisation.  A list of injected single-bit
+    flips (fault model of Section 2.2) is applied to the named fp32 intermediates.
+
+Readings of passages where the paper is silent or inconsistent (each is also
+listed in the design notes of the repository):
+
+* The checksum fold of eq. (13)/(14) is taken as a stride-s fold, as the text
+  after eq. (16) states: check1[i][c] = sum_l S[i][c + s*l].
+* The fold count of the S / P checksums is the number of key columns of the
+  tile divided by s (the paper's ceil(d/8) equals it only when the tile width
+  equals d); the O checksums fold d/s features.
+* With weights l+1 in the second checksum the residual ratio is l+1, so the
+  located fold is round(ratio) - 1.
+* The product-form comparison of Algorithm 1 is evaluated as a log-ratio
+      lambda = ln prod_l P_l - (scale * check1_eff - n_valid * m)
+    , the same identity, defined where a product of many small exponentials
+  leaves the floating-point range.  It is computed as
+      sum_l (ln P_l - x_l) - scale * R1,  R1 = check1 - sum_l S_l,
+  and ln P_l - x_l is taken as exactly zero for an element that still holds the
+  value the exponential produced.
+* A detected class is a linear (GEMM I / subtraction) fault when
+  scale*|R1| > eps1/2 and an exponentiation fault otherwise.  After a linear
+  correction the row's maximum and exponentials for that tile are recomputed
+  ("correct EXP with recomputation").
+* Restoring an element is done by reconstruction (checksum minus the other
+  folds), which equals "adding the residual" algebraically but never reuses a
+  corrupted, possibly infinite, value.
+* The lower bound of the row-sum uses the *local* maximum of each key tile,
+  carried with the same rescale as the row-sum; the upper bound is the number
+  of unmasked keys of the row; both get a relative slack delta_l and equality is
+  allowed (a single key gives bound = sum = 1).
+* A causal mask is not mentioned in the paper.  Masked entries take no part in
+  max / exp / sums; the linear residual uses the whole raw tile; the product
+  check uses the checksum minus the masked raw scores and the count of unmasked
+  folds.  Key tiles with no unmasked entry for a row are skipped for that row.
+* The softmax scale is applied inside x = scale*S - m; the S stage is the raw
+  accumulator.  Thresholds are in logit units / normalised-output units.
+
+Thresholds (eps1, tau_o, delta_l) are this repository's choices: the paper's own
+values (0.48 absolute, 7e-6 relative) belong to its one-word fp16 checksums and
+carry a 5.9% false-alarm rate.  Which faults the paper's code would flag at a
+given threshold is therefore "parity unpinned"; everything else in this file is
+pinned by tests against closed forms, invariants and brute force.
+"""
+from __future__ import annotations
+
+import dataclasses
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+ST_S, ST_EXP, ST_ROWSUM, ST_OACC = 0, 1, 2, 3
+CHECK_S, CHECK_EXP, CHECK_L, CHECK_O = 0, 1, 2, 3
+
+
+@dataclasses.dataclass
+class Params:
+    scale: float
+    causal: bool
+    block_n: int                       # key-tile width B_c
+    stride: int = 8                    # s of eq. (13)
+    eps1: float = 0.03                 # unified product check, log-ratio units
+    tau_o: float = 0.75 * 2.0 ** -9    # final sum check, normalised-output units
+    delta_l: float = 2.0 ** -10        # relative slack of the row-sum range
+    correct: bool = True               # False: detect and locate only
+
+
+def bitflip32(x: float, bit: int) -> float:
+    """Value of x after rounding to fp32 and inverting one bit of the encoding."""
+    u = np.array([x], dtype=np.float64).astype(np.float32).view(np.uint32)
+    u ^= np.uint32(1 << bit)
+    with np.errstate(all="ignore"):
+        return float(u.view(np.float32)[0])
+
+
+# ----------------------------------------------------------------------------
+# (1) the definition
+# ----------------------------------------------------------------------------
+
+def attention_clean(Q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: float,
+                    causal: bool, row_idx: Optional[np.ndarray] = None) -> np.ndarray:
+    """softmax(scale*Q K^T + mask) V for the given query rows (eq. (8), right side).
+
+    Q: [n, d] float64 rows whose global indices are ``row_idx`` (default 0..n-1);
+    K, V: [N, d] float64.
+    """
+    n = Q.shape[0]
+    N = K.shape[0]
+    if row_idx is None:
+        row_idx = np.arange(n)
+    out = np.empty((n, V.shape[1]), np.float64)
+    step = max(1, (1 << 22) // max(N, 1))
+    for a in range(0, n, step):
+        z = slice(a, min(n, a + step))
+        S = scale * (Q[z] @ K.T)
+        if causal:
+            S = np.where(np.arange(N)[None, :] <= row_idx[z, None], S, -np.inf)
+        S = S - S.max(axis=1, keepdims=True)
+        P = np.exp(S)
+        out[z] = (P / P.sum(axis=1, keepdims=True)) @ V
+    return out
+
+
+# ----------------------------------------------------------------------------
+# (2) tensor checksums, eq. (13)-(16)
+# ----------------------------------------------------------------------------
+
+def encode_k(Kj: np.ndarray, s: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Checksums of a key tile: c1[c,:] = sum_l K[c+s*l,:], c2 with weight l+1."""
+    Bc, d = Kj.shape
+    K3 = Kj.reshape(Bc // s, s, d)
+    w = np.arange(1, Bc // s + 1, dtype=np.float64)[:, None, None]
+    return K3.sum(axis=0), (w * K3).sum(axis=0)
+
+
+def encode_v(Vj: np.ndarray, s: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Checksums of a value tile: c1[:,c] = sum_l V[:,c+s*l], c2 with weight l+1."""
+    Bc, d = Vj.shape
+    V3 = Vj.reshape(Bc, d // s, s)
+    w = np.arange(1, d // s + 1, dtype=np.float64)[None, :, None]
+    return V3.sum(axis=1), (w * V3).sum(axis=1)
+
+
+def fold(X: np.ndarray, s: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Strided sums of the columns of X: sum_l X[:,c+s*l] and sum_l (l+1) X[:,c+s*l]."""
+    n, W = X.shape
+    X3 = X.reshape(n, W // s, s)
+    w = np.arange(1, W // s + 1, dtype=np.float64)[None, :, None]
+    with np.errstate(all="ignore"):
+        return X3.sum(axis=1), (w * X3).sum(axis=1)
+
+
+def locate_and_restore(x: np.ndarray, chk1: float, chk2: float) -> Tuple[int, float]:
+    """Strided-ABFT location and repair of one class (text after eq. (16)).
+
+    x: the folds of one class (one row); chk1, chk2: its two checksum values.
+    Returns (fold index, restored value); fold index -1 when no single element
+    can be named.
+    """
+    n = x.shape[0]
+    with np.errstate(all="ignore"):
+        r1 = chk1 - x.sum()
+        r2 = chk2 - (np.arange(1, n + 1) * x).sum()
+        ratio = r2 / r1
+    lstar = -1
+    if np.isfinite(ratio):
+        cand = int(np.rint(ratio)) - 1
+        if 0 <= cand < n:
+            lstar = cand
+    else:
+        bad = np.flatnonzero(~np.isfinite(x))
+        if bad.size == 1:
+            lstar = int(bad[0])
+    if lstar < 0:
+        return -1, 0.0
+    rest = np.delete(x, lstar).sum()
+    return lstar, float(chk1 - rest)
+
+
+# ----------------------------------------------------------------------------
+# (3) Algorithm 1
+# ----------------------------------------------------------------------------
+
+Fault = Tuple[int, int, int, int, int]     # (stage, kv_tile, row, col, bit)
+Event = Tuple[int, int, int, int]          # (check, kv_tile, row, col)
+
+
+def efta_rows(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
+              prm: Params, faults: Sequence[Fault] = (),
+              max_shift: Optional[Dict[Tuple[int, int], float]] = None
+              ) -> Tuple[np.ndarray, List[Event], Dict[str, float]]:
+    """Algorithm 1 for query rows ``row_idx`` of one head.
+
+    Q: [n, d] float64 (rows row_idx of the head's query matrix), K, V: [N, d].
+    Returns (O [n, d], sorted events, diagnostics).  Diagnostics hold the largest
+    check statistic over all evaluated checks relative to its threshold
+    (``lambda_ratio``, ``o_ratio``) and the smallest relative distance of a final
+    row-sum to its range boundaries (``l_distance``); the fault generator uses
+    them to keep clear of decisions that hinge on rounding.
+
+    ``max_shift`` maps (kv_tile, row) to an error added to the running maximum the
+    moment it is formed (Section 3.4, case 1: such an error needs no protection
+    because it cancels between numerator and denominator); tests use it to show
+    exactly that.
+    """
+    s, Bc, sc = prm.stride, prm.block_n, prm.scale
+    n, d = Q.shape
+    N = K.shape[0]
+    assert Bc % s == 0 and d % s == 0
+    nK, nV = Bc // s, d // s
+    row_idx = np.asarray(row_idx, dtype=np.int64)
+    pos = {int(r): i for i, r in enumerate(row_idx)}
+    by_tile: Dict[Tuple[int, int], List[Tuple[int, int, int]]] = {}
+    for (st, kt, row, col, bit) in faults:
+        if int(row) in pos:
+            by_tile.setdefault((int(st), int(kt)), []).append((pos[int(row)], int(col), int(bit)))
+
+    m = np.full(n, -np.inf)
+    ell = np.zeros(n)
+    lower = np.zeros(n)
+    Ot = np.zeros((n, d))
+    Oc1 = np.zeros((n, s))
+    Oc2 = np.zeros((n, s))
+    events: List[Event] = []
+    lam_ratio = 0.0
+    n_tiles = (N + Bc - 1) // Bc
+
+    for j in range(n_tiles):
+        k0 = j * Bc
+        act = np.flatnonzero(row_idx >= k0) if prm.causal else np.arange(n)
+        if act.size == 0:
+            break
+        keys = k0 + np.arange(Bc)
+        Kj = np.zeros((Bc, d)); Vj = np.zeros((Bc, d))
+        kv = min(N, k0 + Bc) - k0
+        Kj[:kv] = K[k0:k0 + kv]; Vj[:kv] = V[k0:k0 + kv]
+        valid = np.broadcast_to(keys[None, :] < N, (act.size, Bc)).copy()
+        if prm.causal:
+            valid &= keys[None, :] <= row_idx[act, None]
+
+        # encode (Algorithm 1, "Encode tensor checksum")
+        Kc1, Kc2 = encode_k(Kj, s)
+        Vc1, Vc2 = encode_v(Vj, s)
+        # GEMM I
+        Qa = Q[act]
+        S = Qa @ Kj.T
+        Sc1 = Qa @ Kc1.T
+        Sc2 = Qa @ Kc2.T
+        loc = {int(a): i for i, a in enumerate(act)}
+        for (ri, col, bit) in by_tile.get((ST_S, j), []):
+            if ri in loc:
+                S[loc[ri], col - k0] = bitflip32(S[loc[ri], col - k0], bit)
+
+        def softmax_part(Srows, vrows, m_old):
+            with np.errstate(all="ignore"):
+                mh = np.where(vrows, sc * Srows, -np.inf).max(axis=1)
+                mn = np.maximum(m_old, mh)
+                x = sc * Srows - mn[:, None]
+                P = np.where(vrows, np.exp(x), 0.0)
+            return mh, mn, x, P
+
+        # reduce max, element-wise exp
+        m_hat, m_new, x, P = softmax_part(S, valid, m[act])
+        for (jt, row), dm in (max_shift or {}).items():
+            if jt == j and int(row) in pos and pos[int(row)] in loc:
+                i = loc[pos[int(row)]]
+                m_new[i] += dm
+                x[i] = sc * S[i] - m_new[i]
+                P[i] = np.where(valid[i], np.exp(x[i]), 0.0)
+        touched = np.zeros_like(valid)
+        for (ri, col, bit) in by_tile.get((ST_EXP, j), []):
+            if ri in loc and valid[loc[ri], col - k0]:
+                P[loc[ri], col - k0] = bitflip32(P[loc[ri], col - k0], bit)
+                touched[loc[ri], col - k0] = True
+
+        # unified verification of GEMM I, subtraction and exp
+        with np.errstate(all="ignore"):
+            sum1, _ = fold(S, s)
+            R1 = Sc1 - sum1
+            e = np.where(touched & valid, np.log(P) - x, 0.0)
+            E, _ = fold(e, s)
+            lam = E - sc * R1
+        has_valid = valid.reshape(act.size, nK, s).any(axis=1)
+        with np.errstate(invalid="ignore"):
+            ok = np.abs(lam) <= prm.eps1
+        det = has_valid & ~ok
+        fin = has_valid & np.isfinite(lam)
+        if fin.any():
+            lam_ratio = max(lam_ratio, float(np.abs(lam[fin]).max()) / prm.eps1)
+        if (has_valid & ~np.isfinite(lam)).any():
+            lam_ratio = np.inf
+        redo = []
+        for (i, c) in zip(*np.nonzero(det)):
+            cols = c + s * np.arange(nK)
+            with np.errstate(invalid="ignore"):
+                linear = not (sc * abs(R1[i, c]) <= prm.eps1 / 2)
+            if linear:
+                lstar, val = locate_and_restore(S[i, cols], Sc1[i, c], Sc2[i, c])
+                col = k0 + int(cols[lstar]) if lstar >= 0 else -1
+                events.append((CHECK_S, j, int(row_idx[act[i]]), col))
+                if prm.correct and lstar >= 0:
+                    S[i, cols[lstar]] = val
+                    redo.append(i)
+            else:
+                with np.errstate(all="ignore"):
+                    good = np.exp(x[i, cols])
+                for l in range(nK):
+                    if valid[i, cols[l]] and touched[i, cols[l]] and P[i, cols[l]] != good[l]:
+                        events.append((CHECK_EXP, j, int(row_idx[act[i]]), k0 + int(cols[l])))
+                        if prm.correct:
+                            P[i, cols[l]] = good[l]
+        for i in sorted(set(redo)):
+            mh, mn, xx, PP = softmax_part(S[i:i + 1], valid[i:i + 1], m[act[i]:act[i] + 1])
+            m_hat[i], m_new[i], x[i], P[i] = mh[0], mn[0], xx[0], PP[0]
+
+        # reduce sum, GEMM II with rescale
+        with np.errstate(all="ignore"):
+            alpha = np.exp(m[act] - m_new)
+            ell[act] = alpha * ell[act] + P.sum(axis=1)
+            lower[act] = alpha * lower[act] + np.where(np.isfinite(m_hat), np.exp(m_hat - m_new), 0.0)
+            for (ri, col, bit) in by_tile.get((ST_ROWSUM, j), []):
+                ell[ri] = bitflip32(ell[ri], bit)
+            Ot[act] = alpha[:, None] * Ot[act] + P @ Vj
+            Oc1[act] = alpha[:, None] * Oc1[act] + P @ Vc1
+            Oc2[act] = alpha[:, None] * Oc2[act] + P @ Vc2
+            for (ri, col, bit) in by_tile.get((ST_OACC, j), []):
+                Ot[ri, col] = bitflip32(Ot[ri, col], bit)
+        m[act] = m_new
+
+    # range restriction of the row-sum
+    U = np.minimum(row_idx + 1, N).astype(np.float64) if prm.causal else np.full(n, float(N))
+    with np.errstate(all="ignore"):
+        in_range = (lower * (1 - prm.delta_l) <= ell) & (ell <= U * (1 + prm.delta_l))
+        dist = np.minimum(np.abs(ell / (lower * (1 - prm.delta_l)) - 1), np.abs(ell / (U * (1 + prm.delta_l)) - 1))
+    dist = np.where(np.isfinite(dist), dist, np.inf)
+    for i in np.flatnonzero(~in_range):
+        events.append((CHECK_L, -1, int(row_idx[i]), 0))
+        if prm.correct:
+            ell[i] = lower[i]
+    # normalisation
+    with np.errstate(all="ignore"):
+        O = Ot / ell[:, None]
+        C1 = Oc1 / ell[:, None]
+        C2 = Oc2 / ell[:, None]
+        # unified verification of GEMM II, rescale and normalisation
+        sum1, _ = fold(O, s)
+        R = C1 - sum1
+        okO = np.abs(R) <= prm.tau_o
+    finR = np.isfinite(R)
+    o_ratio = float(np.abs(R[finR]).max()) / prm.tau_o if finR.any() else 0.0
+    if (~finR).any():
+        o_ratio = np.inf
+    for (i, c) in zip(*np.nonzero(~okO)):
+        cols = c + s * np.arange(nV)
+        lstar, val = locate_and_restore(O[i, cols], C1[i, c], C2[i, c])
+        events.append((CHECK_O, -1, int(row_idx[i]), int(cols[lstar]) if lstar >= 0 else -1))
+        if prm.correct and lstar >= 0:
+            O[i, cols[lstar]] = val
+    diag = {"lambda_ratio": float(lam_ratio), "o_ratio": float(o_ratio),
+            "l_distance": float(dist.min()) if n else np.inf}
+    return O, sorted(events), diag
+
+
+def fault_is_robust(diag: Dict[str, float], band: float = 4.0, l_band: float = 2.0 ** -11) -> bool:
+    """True when no check decision of the run sits near its threshold.
+
+    Used by the fault generator: a candidate fault is kept only if every check
+    statistic is either below threshold/band or above threshold*band, and the
+    final row-sum is further than ``l_band`` (relative) from both range bounds.
+    """
+    for key in ("lambda_ratio", "o_ratio"):
+        r = diag[key]
+        if 1.0 / band <= r <= band:
+            return False
+    return diag["l_distance"] > l_band
+
+
+def fp32_is_fragile(x: float, stage: int) -> bool:
+    """True when the fp32 value x sits so close to a power of two (or to zero, or to
+    the bottom of the normal range) that an fp32 evaluation of the same quantity in
+    another summation order could land in the neighbouring binade, which would
+    change what a flipped exponent or mantissa bit does to it."""
+    if not np.isfinite(x) or x == 0.0:
+        return True
+    ax = abs(float(x))
+    if ax < 2.0 ** -100:
+        return True
+    mant, ex = np.frexp(ax)                    # ax = mant * 2**ex, mant in [0.5, 1)
+    gap = min(mant - 0.5, 1.0 - mant) * 2.0 ** ex   # absolute distance to a binade edge
+    if stage == ST_S:
+        return gap < 2.0 ** -11                # raw scores: absolute accumulation noise
+    rel = 2.0 ** -14 if stage == ST_EXP else 2.0 ** -9
+    return gap < rel * ax

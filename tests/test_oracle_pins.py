@@ -1,0 +1,392 @@
+"""Pins for the CPU oracle: closed forms, invariants, library routines and brute force.
+
+Each test checks the oracle against something other than itself, chosen so that a
+dropped term, a wrong sign or index, or a transposed operand in the oracle fails
+at least one of them.  No GPU is needed.
+"""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import efta_oracle as orc
+from oracle.efta_oracle import (CHECK_EXP, CHECK_L, CHECK_O, CHECK_S, ST_EXP, ST_OACC,
+                                ST_ROWSUM, ST_S, Params, attention_clean, bitflip32,
+                                efta_rows, encode_k, encode_v, fold, locate_and_restore)
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def _rand(N, d, seed, scale=1.0):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal((N, d)) * scale, rng.standard_normal((N, d)) * scale,
+            rng.standard_normal((N, d)) * scale)
+
+
+# ---------------------------------------------------------------- definition
+
+def _parse_rows(txt):
+    def val(t):
+        t = t.strip()
+        return math.log(float(t[2:])) if t.startswith("ln") else float(t)
+    return np.array([[val(t) for t in row.split(",")] for row in txt.split("/")], dtype=np.float64)
+
+
+def test_clean_against_printed_closed_forms():
+    """eq. (8): exact rational softmax weights, expected O written by hand."""
+    n = 0
+    for line in open(os.path.join(HERE, "golden", "softmax_closed_form.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, causal, scale, q, k, v, o = [f.strip() for f in line.split(";")]
+        Q, K, V, O = map(_parse_rows, (q, k, v, o))
+        got = attention_clean(Q, K, V, float(scale), bool(int(causal)))
+        assert np.allclose(got, O, rtol=0, atol=1e-13), name
+        prm = Params(scale=float(scale), causal=bool(int(causal)), block_n=8)
+        Kp = np.vstack([K, np.zeros((0, K.shape[1]))])
+        # the tiled algorithm needs d % 8 == 0: pad the feature axis with zeros
+        pad = lambda X: np.hstack([X, np.zeros((X.shape[0], 8 - X.shape[1]))])
+        got2, ev, _ = efta_rows(pad(Q), np.arange(Q.shape[0]), pad(Kp), pad(V), prm)
+        assert ev == [] and np.allclose(got2[:, :O.shape[1]], O, rtol=0, atol=1e-13), name
+        n += 1
+    assert n == 5
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_clean_against_library_sdpa(causal):
+    torch = pytest.importorskip("torch")
+    Q, K, V = _rand(96, 32, 1)
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(Q)[None, None], torch.from_numpy(K)[None, None], torch.from_numpy(V)[None, None],
+        is_causal=causal, scale=0.3)[0, 0].numpy()
+    got = attention_clean(Q, K, V, 0.3, causal)
+    assert np.abs(got - ref).max() < 1e-13
+
+
+def test_clean_invariants():
+    """Softmax rows sum to one; colsum(P V) = colsum(P) V; colsum(Q K^T) = colsum(Q) K^T."""
+    Q, K, V = _rand(40, 16, 2)
+    ones = attention_clean(Q, K, np.ones((40, 16)), 0.25, True)
+    assert np.abs(ones - 1).max() < 1e-14
+    P = attention_clean(Q, K, np.eye(40), 0.25, False)          # V = I returns P itself
+    assert np.abs(P.sum(axis=1) - 1).max() < 1e-14
+    O = attention_clean(Q, K, V, 0.25, False)
+    assert np.abs(O.sum(axis=0) - P.sum(axis=0) @ V).max() < 1e-13
+    # a permutation of the keys (with their values) must not change O: catches index slips
+    perm = np.random.default_rng(3).permutation(40)
+    assert np.abs(attention_clean(Q, K[perm], V[perm], 0.25, False) - O).max() < 1e-13
+    # transposition slip: scores must be Q K^T, not K Q^T -> one-hot query picks a K column
+    Q1 = np.zeros((1, 16)); Q1[0, 3] = 1.0
+    w = attention_clean(Q1, K, np.eye(40), 1.0, False)[0]
+    e = np.exp(K[:, 3] - K[:, 3].max())
+    assert np.abs(w - e / e.sum()).max() < 1e-14
+    S = Q @ K.T
+    assert np.abs(S.sum(axis=0) - Q.sum(axis=0) @ K.T).max() < 1e-12
+
+
+# ---------------------------------------------------------------- tiled recurrence
+
+@pytest.mark.parametrize("N,d,Bc,causal", [(128, 64, 64, False), (128, 64, 32, True), (200, 16, 64, True),
+                                           (77, 8, 16, False), (64, 128, 128, True), (1, 8, 8, True)])
+def test_tiled_equals_definition(N, d, Bc, causal):
+    """eq. (2)-(8): the online recurrence with checksums attached reaches the definition,
+    raises no flag, and keeps every check statistic at rounding level."""
+    Q, K, V = _rand(N, d, 10 + N)
+    prm = Params(scale=d ** -0.5, causal=causal, block_n=Bc)
+    O, ev, dg = efta_rows(Q, np.arange(N), K, V, prm)
+    assert ev == []
+    assert np.abs(O - attention_clean(Q, K, V, prm.scale, causal)).max() < 1e-12
+    assert dg["lambda_ratio"] < 1e-9 and dg["o_ratio"] < 1e-9
+    # a subset of rows gives the same rows
+    rows = np.arange(N)[::3]
+    O2, _, _ = efta_rows(Q[rows], rows, K, V, prm)
+    assert np.abs(O2 - O[rows]).max() < 1e-13
+
+
+# ---------------------------------------------------------------- checksums
+
+def test_encode_closed_forms():
+    """eq. (13)-(16): products with the encoded tiles equal strided sums of the plain product."""
+    rng = np.random.default_rng(5)
+    Qi = rng.standard_normal((7, 24)); Kj = rng.standard_normal((32, 24)); Vj = rng.standard_normal((32, 24))
+    Kc1, Kc2 = encode_k(Kj, 8)
+    S = Qi @ Kj.T
+    for c in range(8):
+        assert np.allclose(Qi @ Kc1[c], sum(S[:, c + 8 * l] for l in range(4)), atol=1e-12)
+        assert np.allclose(Qi @ Kc2[c], sum((l + 1) * S[:, c + 8 * l] for l in range(4)), atol=1e-12)
+    f1, f2 = fold(S, 8)
+    assert np.allclose(f1, Qi @ Kc1.T, atol=1e-12) and np.allclose(f2, Qi @ Kc2.T, atol=1e-12)
+    P = rng.random((7, 32))
+    Vc1, Vc2 = encode_v(Vj, 8)
+    Ot = P @ Vj
+    for c in range(8):
+        assert np.allclose(P @ Vc1[:, c], sum(Ot[:, c + 8 * l] for l in range(3)), atol=1e-12)
+        assert np.allclose(P @ Vc2[:, c], sum((l + 1) * Ot[:, c + 8 * l] for l in range(3)), atol=1e-12)
+
+
+def test_classical_abft_locate_correct():
+    """eq. (9), (10): one checksum class per column (stride 1 fold over all rows)."""
+    rng = np.random.default_rng(6)
+    A = rng.standard_normal((6, 5)); B = rng.standard_normal((5, 4))
+    C = A @ B
+    c1 = np.ones(6) @ A @ B
+    c2 = np.arange(1, 7) @ A @ B
+    for i in range(6):
+        for j in range(4):
+            for delta in (0.5, -3.0, 1e6):
+                Cb = C.copy(); Cb[i, j] += delta
+                # the paper's index formula: (c2' - c2) / (c1' - c1) names row i (1-based weight)
+                ratio = (np.arange(1, 7) @ Cb[:, j] - c2[j]) / (Cb[:, j].sum() - c1[j])
+                assert round(ratio) - 1 == i
+                l, val = locate_and_restore(Cb[:, j], c1[j], c2[j])
+                assert l == i and abs(val - C[i, j]) < 1e-9 * max(1, abs(delta))
+
+
+def test_strided_locate_bruteforce():
+    """Text after eq. (16): every position of a tile, several error sizes incl. Inf/NaN."""
+    rng = np.random.default_rng(7)
+    Qi = rng.standard_normal((4, 16)); Kj = rng.standard_normal((32, 16))
+    S = Qi @ Kj.T
+    Kc1, Kc2 = encode_k(Kj, 8)
+    Sc1, Sc2 = Qi @ Kc1.T, Qi @ Kc2.T
+    for i in range(4):
+        for col in range(32):
+            for delta in (1.0, -0.01, 1e30, np.inf, -np.inf, np.nan):
+                Sb = S.copy(); Sb[i, col] = Sb[i, col] + delta
+                c = col % 8
+                cols = c + 8 * np.arange(4)
+                l, val = locate_and_restore(Sb[i, cols], Sc1[i, c], Sc2[i, c])
+                assert cols[l] == col
+                assert abs(val - S[i, col]) < 1e-12
+
+
+def test_strided_multi_error_rows():
+    """Errors in distinct stride-8 classes of one row are all repaired; two in one class are
+    detected but cannot be located (the limitation the paper states)."""
+    Q, K, V = _rand(64, 16, 8)
+    prm = Params(scale=0.25, causal=False, block_n=32)
+    clean = attention_clean(Q, K, V, 0.25, False)
+    faults = [(ST_S, 1, 5, 32 + c + 8 * (c % 4), 28) for c in range(8)]    # 8 classes, row 5, tile 1
+    O, ev, _ = efta_rows(Q, np.arange(64), K, V, prm, faults)
+    assert ev == sorted((CHECK_S, 1, 5, f[3]) for f in faults)
+    assert np.abs(O - clean).max() < 1e-11
+    same = [(ST_S, 0, 9, 3, 29), (ST_S, 0, 9, 19, 29)]                     # both class 3
+    O, ev, _ = efta_rows(Q, np.arange(64), K, V, prm, same)
+    assert len(ev) >= 1 and ev[0][0] == CHECK_S                            # noticed ...
+    assert np.abs(O[9] - clean[9]).max() > 1e-6                            # ... but not repaired
+
+
+# ---------------------------------------------------------------- softmax protection
+
+def test_case1_max_error_cancels():
+    """Section 3.4, case 1: an error in the row maximum cancels between numerator and
+    denominator.  (A maximum that ends the loop too LOW inflates the row-sum by the same factor,
+    which the upper range bound may then notice; the shifts below stay inside the range.)"""
+    Q, K, V = _rand(96, 16, 9)
+    prm = Params(scale=0.25, causal=False, block_n=32)
+    base, _, _ = efta_rows(Q, np.arange(96), K, V, prm)
+    for dm in (0.7, -1.0, 11.0):
+        O, ev, dg = efta_rows(Q, np.arange(96), K, V, prm, max_shift={(1, 50): dm, (0, 7): abs(dm), (2, 90): dm})
+        assert ev == [] and np.abs(O - base).max() < 1e-12
+        assert dg["lambda_ratio"] < 1e-9
+
+
+def _row_state(q, K, scale, Bc, j, row, causal):
+    """Independent evaluation of m (running max through tile j) and the tile's scores."""
+    hi = min(K.shape[0], (j + 1) * Bc)
+    keys = np.arange(hi)
+    ok = keys <= row if causal else np.ones(hi, bool)
+    s_all = scale * (K[:hi] @ q)
+    m = s_all[ok].max()
+    return m, s_all[j * Bc:hi], ok[j * Bc:hi]
+
+
+def test_case2_product_identity_and_signatures():
+    """prod_l exp(S_l - m) = exp(check1 - n*m) on clean data (masked classes included), and the
+    oracle's log-ratio statistic equals ln(P'/P) for an exp fault and scale*delta for a score fault."""
+    N, d, Bc = 96, 16, 32
+    Q, K, V = _rand(N, d, 11)
+    scale = 0.25
+    for causal in (False, True):
+        prm = Params(scale=scale, causal=causal, block_n=Bc)
+        for (row, j) in ((40, 1), (95, 2), (33, 1)):
+            m, sj, ok = _row_state(Q[row], K, scale, Bc, j, row, causal)
+            Kc1, _ = encode_k(K[j * Bc:(j + 1) * Bc], 8)
+            for c in range(8):
+                cols = c + 8 * np.arange(Bc // 8)
+                okc = ok[cols]
+                if not okc.any():
+                    continue
+                prod = np.prod(np.exp(sj[cols][okc] - m))
+                chk_eff = scale * (Q[row] @ Kc1[c]) - sj[cols][~okc].sum()
+                assert abs(prod / np.exp(chk_eff - okc.sum() * m) - 1) < 1e-12
+            col = j * Bc + (3 if not causal else 1)
+            p = math.exp(sj[col - j * Bc] - m)
+            for bit in (20, 22, 24, 30):
+                pf = bitflip32(p, bit)
+                _, ev, dg = efta_rows(Q[row:row + 1], np.array([row]), K, V, prm, [(ST_EXP, j, row, col, bit)])
+                want = abs(math.log(pf / p)) if 0 < pf < np.inf else np.inf   # incl. the fp32 rounding of P
+                if np.isfinite(want):
+                    assert abs(dg["lambda_ratio"] * prm.eps1 - want) < 1e-9 * max(1, want)
+                assert ((CHECK_EXP, j, row, col) in ev) == (want > prm.eps1)
+            s_raw = float(Q[row] @ K[col])
+            for bit in (21, 25, 29):
+                delta = bitflip32(s_raw, bit) - float(np.float32(s_raw))
+                _, ev, dg = efta_rows(Q[row:row + 1], np.array([row]), K, V, prm, [(ST_S, j, row, col, bit)])
+                # the fp32 rounding of the score is itself part of the injected error
+                delta_total = bitflip32(s_raw, bit) - s_raw
+                assert abs(dg["lambda_ratio"] * prm.eps1 - scale * abs(delta_total)) < 1e-6 * max(1.0, scale * abs(delta))
+                assert ((CHECK_S, j, row, col) in ev) == (scale * abs(delta_total) > prm.eps1)
+
+
+def test_case2_minimum_signature():
+    """Any flip of bits 20..30 of a normal fp32 in (0, 1] moves its log by more than 2*eps1."""
+    worst = np.inf
+    for mant in np.linspace(1.0, 2.0, 4097)[:-1]:
+        for ex in (-1, -20, -60):
+            p = float(np.float32(mant * 2.0 ** ex))
+            for bit in range(20, 31):
+                pf = bitflip32(p, bit)
+                if 0 < pf < np.inf:
+                    worst = min(worst, abs(math.log(pf / p)))
+    assert worst >= math.log(1 + 2.0 ** -4) - 1e-12
+    assert worst > 2 * Params(scale=1, causal=False, block_n=8).eps1
+
+
+def test_case3_rowsum_bounds_and_counterexample():
+    """lower <= l <= upper on assorted inputs, equality for a single key, and the running-max
+    reading of the lower bound is not a bound."""
+    for seed, scale, causal in ((1, 0.1, False), (2, 3.0, True), (3, 1.0, True)):
+        Q, K, V = _rand(80, 8, 20 + seed)
+        K[::7] *= 8
+        prm = Params(scale=scale, causal=causal, block_n=16, delta_l=0.0)
+        _, ev, _ = efta_rows(Q, np.arange(80), K, V, prm)
+        assert ev == []                      # with zero slack: lower <= l <= upper exactly
+    # single unmasked key: lower = l = upper = 1 (row 0 of a causal head), slack zero, no flag
+    prm = Params(scale=1.0, causal=True, block_n=8, delta_l=0.0)
+    Q, K, V = _rand(8, 8, 30)
+    O, ev, _ = efta_rows(Q[:1], np.array([0]), K, V, prm)
+    assert ev == [] and np.allclose(O[0], V[0], atol=1e-14)
+    # counter-example: one dominant score in the first of four tiles.
+    scores = np.full(32, -30.0); scores[0] = 0.0
+    l_true = np.exp(scores).sum()
+    run_max = np.maximum.accumulate(scores.reshape(4, 8).max(axis=1))
+    loc_max = scores.reshape(4, 8).max(axis=1)
+    assert np.exp(run_max - run_max[-1]).sum() > l_true          # "bound" of 4 above l ~ 1
+    assert np.exp(loc_max - run_max[-1]).sum() <= l_true         # local maxima: a true bound
+
+
+def test_case3_substitution_closed_form():
+    """When the row-sum leaves its range it is replaced by the lower bound, so the row of O is
+    the clean row times l_true / lower."""
+    N, d, Bc = 64, 8, 16
+    Q, K, V = _rand(N, d, 40)
+    prm = Params(scale=0.5, causal=False, block_n=Bc)
+    clean = attention_clean(Q, K, V, 0.5, False)
+    row = 17
+    s = 0.5 * (K @ Q[row]); m = s.max()
+    l_true = np.exp(s - m).sum()
+    lower = np.exp(s.reshape(N // Bc, Bc).max(axis=1) - m).sum()
+    O, ev, _ = efta_rows(Q, np.arange(N), K, V, prm, [(ST_ROWSUM, 3, row, 0, 30)])
+    assert ev == [(CHECK_L, -1, row, 0)]
+    assert np.abs(O[row] - clean[row] * l_true / lower).max() < 1e-12
+    others = np.delete(np.arange(N), row)
+    assert np.abs(O[others] - clean[others]).max() < 1e-12
+
+
+def test_oacc_fault_located_and_restored():
+    N, d, Bc = 64, 32, 16
+    Q, K, V = _rand(N, d, 41)
+    prm = Params(scale=0.3, causal=True, block_n=Bc)
+    clean = attention_clean(Q, K, V, 0.3, True)
+    for (row, col, kt, bit) in ((63, 0, 0, 28), (40, 31, 2, 22), (20, 13, 1, 30), (33, 8, 0, 25)):
+        O, ev, dg = efta_rows(Q, np.arange(N), K, V, prm, [(ST_OACC, kt, row, col, bit)])
+        if dg["o_ratio"] > 1:
+            assert ev == [(CHECK_O, -1, row, col)]
+            assert np.abs(O - clean).max() < 1e-10
+        else:
+            assert ev == []
+
+
+# ---------------------------------------------------------------- whole pipeline, brute force
+
+def _exhaustive(stage, rows, N=32, d=16, Bc=16, causal=True):
+    Q, K, V = _rand(N, d, 50)
+    scale = 0.4
+    prm = Params(scale=scale, causal=causal, block_n=Bc)
+    clean = attention_clean(Q, K, V, scale, causal)
+    vmax = np.abs(V).max()
+    n_det = n_tot = 0
+    for row in rows:
+        q = Q[row:row + 1]; ridx = np.array([row])
+        s = scale * (K @ Q[row]); ok = np.arange(N) <= row if causal else np.ones(N, bool)
+        m = s[ok].max(); l_true = np.exp(s[ok] - m).sum()
+        nt = (row if causal else N - 1) // Bc + 1
+        if stage in (ST_S, ST_EXP):
+            targets = [(c // Bc, c) for c in range(row + 1 if causal else N)]
+        elif stage == ST_ROWSUM:
+            targets = [(t, 0) for t in range(nt)]
+        else:
+            targets = [(t, c) for t in range(nt) for c in range(0, d, 3)]
+        for (kt, col) in targets:
+            for bit in range(31):
+                O, ev, dg = efta_rows(q, ridx, K, V, prm, [(stage, kt, row, col, bit)])
+                n_tot += 1
+                dev = np.abs(O[0] - clean[row]).max()
+                if stage == ST_ROWSUM:
+                    if ev:
+                        assert ev == [(CHECK_L, -1, row, 0)]
+                        lower = sum(np.exp(s[t * Bc:(t + 1) * Bc][ok[t * Bc:(t + 1) * Bc]].max() - m) for t in range(nt))
+                        assert np.abs(O[0] - clean[row] * l_true / lower).max() < 1e-10
+                        n_det += 1
+                    else:     # undetected: row is the clean row times l_true / l', l' inside the range
+                        k = np.abs(clean[row]).argmax()
+                        f = O[0, k] / clean[row, k]
+                        assert np.abs(O[0] - f * clean[row]).max() < 1e-10
+                        assert l_true / ((row + 1 if causal else N) * (1 + prm.delta_l)) - 1e-12 <= f
+                    continue
+                if ev:
+                    n_det += 1
+                    want = {ST_S: CHECK_S, ST_EXP: CHECK_EXP, ST_OACC: CHECK_O}[stage]
+                    assert ev == [(want, kt if stage != ST_OACC else -1, row, col)], (ev, row, col, bit)
+                    assert dev < 1e-9, (stage, row, col, bit, dev)
+                else:
+                    assert max(dg["lambda_ratio"], dg["o_ratio"]) <= 1.0
+                    if stage == ST_OACC:
+                        assert dev <= prm.tau_o * (1 + 1e-9)
+                    else:     # one softmax weight moved by a factor within exp(+-eps1)
+                        assert dev <= 2 * vmax * (math.exp(prm.eps1) - 1) * 1.0001
+    return n_det, n_tot
+
+
+def test_exhaustive_bitflips_scores():
+    det, tot = _exhaustive(ST_S, rows=(0, 9, 17, 31))
+    assert tot == (1 + 10 + 18 + 32) * 31 and det > tot // 4
+
+
+def test_exhaustive_bitflips_exp():
+    det, tot = _exhaustive(ST_EXP, rows=(3, 16, 30))
+    assert det > tot // 4
+
+
+def test_exhaustive_bitflips_rowsum():
+    det, tot = _exhaustive(ST_ROWSUM, rows=range(0, 32, 3))
+    assert det > 0
+
+
+def test_exhaustive_bitflips_oacc():
+    det, tot = _exhaustive(ST_OACC, rows=(1, 15, 16, 31), causal=False)
+    assert det > tot // 4
+
+
+# ---------------------------------------------------------------- helper predicates
+
+def test_bitflip_and_fragility_helpers():
+    assert bitflip32(1.0, 22) == 1.5 and bitflip32(1.0, 23) == 0.5 and bitflip32(0.75, 30) > 1e38
+    assert orc.fp32_is_fragile(1.0, ST_EXP) and orc.fp32_is_fragile(0.0, ST_S)
+    assert not orc.fp32_is_fragile(0.75, ST_EXP) and not orc.fp32_is_fragile(3.1, ST_S)
+    assert orc.fp32_is_fragile(4.0001, ST_S) and orc.fp32_is_fragile(1e-40, ST_EXP)
+    assert orc.fault_is_robust({"lambda_ratio": 10.0, "o_ratio": 1e-9, "l_distance": 0.5})
+    assert not orc.fault_is_robust({"lambda_ratio": 1.5, "o_ratio": 1e-9, "l_distance": 0.5})
+    assert not orc.fault_is_robust({"lambda_ratio": 0.0, "o_ratio": 0.0, "l_distance": 1e-5})
