@@ -1,0 +1,139 @@
+/*
+ * ftattn.h -- C ABI of the fault-tolerant fused attention library for AMD MI355X (gfx950).
+ *
+ * The library computes O = softmax(scale * Q K^T + causal mask) V for tensors of shape
+ * [batch, heads, seq, head_dim] (the operand shape of Section 3.1 of "FT-Transformer: Resilient
+ * and Reliable Transformer with End-to-End Fault Tolerant Attention") in one flash-style pass
+ * and carries strided tensor checksums through that pass as Algorithm 1 of the paper
+ * ("EFTA with unified verification", Section 3.4) prescribes:
+ *
+ *   - tensor checksums of every K and V tile with stride 8 and weights 1 and l+1
+ *     (eq. (13), (14));
+ *   - GEMM I with two checksum products (eq. (15), (16)), running max, exp, and ONE
+ *     product-form check per key-tile iteration that covers GEMM I, the subtraction of the
+ *     maximum and the exponentiation (Section 3.4 case 2); a linear fault is located with the
+ *     second checksum and repaired from the first, an exponentiation fault is repaired by
+ *     recomputation;
+ *   - GEMM II with rescale and two checksum products, and ONE sum-form check after the loop
+ *     that covers GEMM II, rescale and normalisation;
+ *   - a range check of the final row-sum between the sum of exponentials of the per-tile
+ *     maxima and the number of unmasked keys, with substitution of the lower bound
+ *     (Section 3.4 case 3 and the "optimized EFTA" paragraph).
+ *
+ * A deterministic fault injector flips chosen bits of chosen fp32 intermediates inside the
+ * kernel (fault model of Section 2.2; one bit flip per attention computation, Section 4.3).
+ *
+ * Conventions
+ *   - All functions return FTATTN_OK (0) or a negative error code and never throw or print.
+ *     After a failure ftattn_last_error() returns a message owned by the context.
+ *   - q, k, v, o are DEVICE pointers owned by the caller: contiguous [batch, heads, seq,
+ *     head_dim], 16-byte aligned.  Everything else passed by pointer is HOST memory.
+ *   - The context owns all device scratch (encoded K / V tiles, fault and event buffers).
+ *     ftattn_forward allocates nothing and is asynchronous on the stream it is given, except
+ *     that a non-empty fault list is uploaded synchronously before the launch.
+ *   - One context serves one shape; calls on one context must not overlap in time.
+ */
+#ifndef FTATTN_H
+#define FTATTN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ftattn_ctx ftattn_ctx; /* opaque, library-owned */
+
+enum { FTATTN_F16 = 0, FTATTN_BF16 = 1, FTATTN_F32 = 2 };
+/* injection stages: which fp32 intermediate a fault hits */
+enum { FTATTN_ST_S = 0, FTATTN_ST_EXP = 1, FTATTN_ST_ROWSUM = 2, FTATTN_ST_OACC = 3 };
+/* checks that can raise an event */
+enum { FTATTN_CHECK_S = 0, FTATTN_CHECK_EXP = 1, FTATTN_CHECK_L = 2, FTATTN_CHECK_O = 3 };
+enum { FTATTN_OK = 0, FTATTN_EINVAL = -1, FTATTN_EUNSUPPORTED = -2, FTATTN_EHIP = -3, FTATTN_ENOMEM = -4 };
+/* ft_mode */
+enum { FTATTN_FT_OFF = 0, FTATTN_FT_CORRECT = 1, FTATTN_FT_DETECT = 2 };
+
+/* tile_flags bits (per [b, h, row tile, key tile]) */
+enum { FTATTN_TF_DET_S = 1, FTATTN_TF_COR_S = 2, FTATTN_TF_DET_EXP = 4, FTATTN_TF_COR_EXP = 8 };
+/* rowtile_flags bits (per [b, h, row tile]) */
+enum { FTATTN_RF_DET_L = 1, FTATTN_RF_COR_L = 2, FTATTN_RF_DET_O = 4, FTATTN_RF_COR_O = 8,
+       FTATTN_RF_EVENT_OVERFLOW = 16 };
+
+typedef struct {
+  uint32_t struct_size;   /* sizeof(ftattn_config), checked */
+  int32_t batch, heads, seq, head_dim; /* head_dim 64 or 128; seq >= 1 (any length) */
+  int32_t in_dtype;       /* FTATTN_F16 | FTATTN_BF16.  bf16 operands are converted to fp16 on
+                             entry (exact for 2^-14 <= |x| <= 65504): the contractions run on
+                             fp16 MFMA with fp32 accumulation for either input type. */
+  int32_t out_dtype;      /* FTATTN_F32, or the input type */
+  int32_t causal;         /* 0 | 1: lower-triangular mask including the diagonal */
+  float softmax_scale;    /* <= 0 selects 1/sqrt(head_dim) */
+  int32_t ft_mode;        /* FTATTN_FT_OFF: same kernel with every check compiled out;
+                             FTATTN_FT_CORRECT: detect, locate, correct;
+                             FTATTN_FT_DETECT: detect and locate, leave values as they are */
+  int32_t stride;         /* checksum stride s of eq. (13); 0 or 8 */
+  int32_t block_m, block_n; /* 0 selects the library's tile sizes; others are rejected unless
+                             supported.  Effective values: ftattn_get_config. */
+  float eps1;             /* threshold of the per-iteration product-form check on
+                             |ln prod P - ln P^c1| (Algorithm 1, first "if"); <= 0 selects 0.03 */
+  float tau_o;            /* threshold of the final sum-form check on the normalised output
+                             (Algorithm 1, last "if"); <= 0 selects 0.75 * 2^-9 */
+  float delta_l;          /* relative slack of the row-sum range check; <= 0 selects 2^-10 */
+  int32_t max_events;     /* capacity of the event log; <= 0 selects 65536 */
+  int32_t device;         /* HIP device ordinal */
+} ftattn_config;
+
+/* One injected soft error: invert bit `bit` (0..31) of the fp32 encoding of
+ *   S      : the raw GEMM I accumulator at (row, col) = (query, key); kv_tile must equal
+ *            col / block_n and the position must not be masked;
+ *   EXP    : exp(scale*S - m) at (row, col), same constraints;
+ *   ROWSUM : the running row-sum of `row` right after the update of iteration kv_tile (col ignored);
+ *   OACC   : the un-normalised output accumulator at (row, col = feature) right after the
+ *            update of iteration kv_tile.
+ * kv_tile must be an iteration that row takes part in (causal rows stop at their diagonal). */
+typedef struct { int32_t b, h, stage, kv_tile, row, col, bit; } ftattn_fault;
+
+typedef struct {
+  int32_t b, h, check;    /* FTATTN_CHECK_* */
+  int32_t kv_tile;        /* key-tile iteration (S, EXP); -1 for the post-loop checks (L, O) */
+  int32_t row;            /* global query index */
+  int32_t col;            /* S, EXP: global key index; O: feature index; L: 0; -1 = not locatable */
+  float residual;         /* S, EXP: log-ratio statistic; L: the offending row-sum; O: sum residual */
+  int32_t action;         /* 1 corrected, 0 detected only */
+} ftattn_event;
+
+/* Views into host memory owned by the context; valid until the next forward / destroy. */
+typedef struct {
+  int32_t n_events;           /* events stored */
+  int32_t n_events_dropped;   /* events that did not fit max_events */
+  const ftattn_event* events; /* sorted by (b, h, check, kv_tile, row, col) */
+  int32_t tiles_m, tiles_n;   /* row tiles and key tiles per head */
+  const uint8_t* tile_flags;     /* [batch, heads, tiles_m, tiles_n], FTATTN_TF_* (from stored events) */
+  const uint8_t* rowtile_flags;  /* [batch, heads, tiles_m], FTATTN_RF_* */
+  const float* residual_max;     /* [batch, heads, tiles_m, 4]: largest fault-free-looking statistic seen:
+                                    0: |prod/expected - 1| of the product check, 1: |sum residual| of the
+                                    O check, 2: row-sum / upper bound, 3: lower bound / row-sum */
+  int64_t recheck_entries;    /* how often a wave left the fast path to re-evaluate a check exactly */
+} ftattn_report_view;
+
+/* Validates cfg, allocates all device scratch for this shape on cfg->device. */
+int ftattn_create(const ftattn_config* cfg, ftattn_ctx** out);
+/* Copies the configuration in effect (defaults resolved: tile sizes, thresholds, scale). */
+int ftattn_get_config(const ftattn_ctx* ctx, ftattn_config* effective);
+/* One attention pass (Algorithm 1, all steps) on `hip_stream` (a hipStream_t, may be NULL).
+ * faults: host array or NULL.  Faults that name a masked / out-of-range position make the call
+ * fail with FTATTN_EINVAL before anything is launched.  With ft_mode OFF a fault list is
+ * still applied (shows the unprotected damage). */
+int ftattn_forward(ftattn_ctx* ctx, const void* q, const void* k, const void* v, void* o,
+                   const ftattn_fault* faults, int32_t n_faults, void* hip_stream);
+/* Waits for the last forward of this context and exposes its flags, residuals and events. */
+int ftattn_report(ftattn_ctx* ctx, ftattn_report_view* out);
+int ftattn_destroy(ftattn_ctx* ctx);
+/* Message of the last failure on this context ("" if none).  ctx may be NULL: returns the
+ * message of the last failed ftattn_create of the calling thread. */
+const char* ftattn_last_error(const ftattn_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FTATTN_H */

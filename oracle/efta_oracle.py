@@ -199,7 +199,8 @@ def efta_rows(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
     check statistic over all evaluated checks relative to its threshold
     (``lambda_ratio``, ``o_ratio``) and the smallest relative distance of a final
     row-sum to its range boundaries (``l_distance``); the fault generator uses
-    them to keep clear of decisions that hinge on rounding.
+    them to keep clear of decisions that hinge on rounding.  ``flipped`` lists
+    (stage, value before the flip) for every fault that was applied.
 
     ``max_shift`` maps (kv_tile, row) to an error added to the running maximum the
     moment it is formed (Section 3.4, case 1: such an error needs no protection
@@ -225,6 +226,7 @@ def efta_rows(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
     Oc1 = np.zeros((n, s))
     Oc2 = np.zeros((n, s))
     events: List[Event] = []
+    flipped: List[Tuple[int, float]] = []     # (stage, value before the flip) of every applied fault
     lam_ratio = 0.0
     n_tiles = (N + Bc - 1) // Bc
 
@@ -252,6 +254,7 @@ def efta_rows(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
         loc = {int(a): i for i, a in enumerate(act)}
         for (ri, col, bit) in by_tile.get((ST_S, j), []):
             if ri in loc:
+                flipped.append((ST_S, float(S[loc[ri], col - k0])))
                 S[loc[ri], col - k0] = bitflip32(S[loc[ri], col - k0], bit)
 
         def softmax_part(Srows, vrows, m_old):
@@ -273,6 +276,7 @@ def efta_rows(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
         touched = np.zeros_like(valid)
         for (ri, col, bit) in by_tile.get((ST_EXP, j), []):
             if ri in loc and valid[loc[ri], col - k0]:
+                flipped.append((ST_EXP, float(P[loc[ri], col - k0])))
                 P[loc[ri], col - k0] = bitflip32(P[loc[ri], col - k0], bit)
                 touched[loc[ri], col - k0] = True
 
@@ -322,11 +326,13 @@ def efta_rows(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
             ell[act] = alpha * ell[act] + P.sum(axis=1)
             lower[act] = alpha * lower[act] + np.where(np.isfinite(m_hat), np.exp(m_hat - m_new), 0.0)
             for (ri, col, bit) in by_tile.get((ST_ROWSUM, j), []):
+                flipped.append((ST_ROWSUM, float(ell[ri])))
                 ell[ri] = bitflip32(ell[ri], bit)
             Ot[act] = alpha[:, None] * Ot[act] + P @ Vj
             Oc1[act] = alpha[:, None] * Oc1[act] + P @ Vc1
             Oc2[act] = alpha[:, None] * Oc2[act] + P @ Vc2
             for (ri, col, bit) in by_tile.get((ST_OACC, j), []):
+                flipped.append((ST_OACC, float(Ot[ri, col])))
                 Ot[ri, col] = bitflip32(Ot[ri, col], bit)
         m[act] = m_new
 
@@ -360,7 +366,7 @@ def efta_rows(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
         if prm.correct and lstar >= 0:
             O[i, cols[lstar]] = val
     diag = {"lambda_ratio": float(lam_ratio), "o_ratio": float(o_ratio),
-            "l_distance": float(dist.min()) if n else np.inf}
+            "l_distance": float(dist.min()) if n else np.inf, "flipped": flipped}
     return O, sorted(events), diag
 
 

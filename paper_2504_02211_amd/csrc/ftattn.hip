@@ -1,0 +1,324 @@
+// Host side of the fault-tolerant fused attention library: the C ABI of include/ftattn.h.
+// Validation, fault bucketing, launches and the report are here; every arithmetic step of
+// the attention pass runs in the kernels of ftattn_device.h.
+#include "ftattn_device.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace ftattn;
+
+struct ftattn_ctx {
+  ftattn_config cfg;          // effective configuration
+  int BH, Ti, Tj, BM, NW, NQ;
+  // device scratch
+  _Float16* qh = nullptr;     // fp16 copy of Q (bf16 input only)
+  _Float16* kc = nullptr;
+  _Float16* vt = nullptr;
+  DevFault* d_faults = nullptr;
+  int32_t* d_fault_off = nullptr;
+  ftattn_event* d_events = nullptr;
+  int32_t* d_ev_count = nullptr;
+  unsigned long long* d_recheck = nullptr;
+  uint32_t* d_resmax = nullptr;
+  int fault_cap = 0;
+  // pinned host staging
+  DevFault* h_faults = nullptr;
+  int32_t* h_fault_off = nullptr;
+  // report storage
+  std::vector<ftattn_event> events;
+  std::vector<uint8_t> tile_flags, rowtile_flags;
+  std::vector<float> resmax;
+  hipStream_t last_stream = nullptr;
+  bool ran = false;
+  std::string err;
+};
+
+static thread_local std::string g_create_err;
+
+static int fail(ftattn_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg; else g_create_err = msg;
+  return code;
+}
+
+#define HIP_TRY(ctx, expr)                                                                      \
+  do {                                                                                          \
+    hipError_t e_ = (expr);                                                                     \
+    if (e_ != hipSuccess)                                                                       \
+      return fail(ctx, e_ == hipErrorOutOfMemory ? FTATTN_ENOMEM : FTATTN_EHIP,                 \
+                  std::string(#expr) + ": " + hipGetErrorString(e_));                           \
+  } while (0)
+
+static void release(ftattn_ctx* c) {
+  if (!c) return;
+  (void)hipFree(c->qh); (void)hipFree(c->kc); (void)hipFree(c->vt); (void)hipFree(c->d_faults);
+  (void)hipFree(c->d_fault_off); (void)hipFree(c->d_events); (void)hipFree(c->d_ev_count);
+  (void)hipFree(c->d_recheck); (void)hipFree(c->d_resmax);
+  if (c->h_faults) (void)hipHostFree(c->h_faults);
+  if (c->h_fault_off) (void)hipHostFree(c->h_fault_off);
+  delete c;
+}
+
+typedef void (*main_fn)(const KArgs);
+
+template <int D, int NW, int NQ>
+static main_fn pick(bool ft, bool causal) {
+  if (ft) return causal ? ftattn_main<D, NW, NQ, true, true> : ftattn_main<D, NW, NQ, true, false>;
+  return causal ? ftattn_main<D, NW, NQ, false, true> : ftattn_main<D, NW, NQ, false, false>;
+}
+
+static main_fn select_kernel(int D, int NW, int NQ, bool ft, bool causal) {
+  if (D == 128) {
+    if (NW == 4 && NQ == 2) return pick<128, 4, 2>(ft, causal);
+    if (NW == 4 && NQ == 1) return pick<128, 4, 1>(ft, causal);
+  } else if (D == 64) {
+    if (NW == 4 && NQ == 2) return pick<64, 4, 2>(ft, causal);
+    if (NW == 4 && NQ == 1) return pick<64, 4, 1>(ft, causal);
+  }
+  return nullptr;
+}
+
+static size_t lds_bytes(int D) { return 2 * (size_t)((BN + CKR) * D * 2 + (D + CKR) * BN * 2); }
+
+extern "C" int ftattn_create(const ftattn_config* cfg, ftattn_ctx** out) {
+  if (!cfg || !out) return fail(nullptr, FTATTN_EINVAL, "null argument");
+  *out = nullptr;
+  if (cfg->struct_size != sizeof(ftattn_config)) return fail(nullptr, FTATTN_EINVAL, "struct_size mismatch");
+  if (cfg->batch < 1 || cfg->heads < 1 || cfg->seq < 1) return fail(nullptr, FTATTN_EINVAL, "batch, heads, seq must be >= 1");
+  if ((long long)cfg->batch * cfg->heads > 65535) return fail(nullptr, FTATTN_EUNSUPPORTED, "batch*heads > 65535");
+  if (cfg->head_dim != 64 && cfg->head_dim != 128) return fail(nullptr, FTATTN_EUNSUPPORTED, "head_dim must be 64 or 128");
+  if (cfg->in_dtype != FTATTN_F16 && cfg->in_dtype != FTATTN_BF16) return fail(nullptr, FTATTN_EINVAL, "in_dtype must be F16 or BF16");
+  if (cfg->out_dtype != FTATTN_F32 && cfg->out_dtype != cfg->in_dtype) return fail(nullptr, FTATTN_EINVAL, "out_dtype must be F32 or the input type");
+  if (cfg->ft_mode < 0 || cfg->ft_mode > 2) return fail(nullptr, FTATTN_EINVAL, "ft_mode out of range");
+  if (cfg->stride != 0 && cfg->stride != 8) return fail(nullptr, FTATTN_EUNSUPPORTED, "stride must be 8");
+  if (cfg->block_n != 0 && cfg->block_n != BN) return fail(nullptr, FTATTN_EUNSUPPORTED, "block_n must be 64");
+  if (cfg->block_m != 0 && cfg->block_m != 128 && cfg->block_m != 256) return fail(nullptr, FTATTN_EUNSUPPORTED, "block_m must be 128 or 256");
+  if (cfg->causal != 0 && cfg->causal != 1) return fail(nullptr, FTATTN_EINVAL, "causal must be 0 or 1");
+
+  ftattn_ctx* c = new (std::nothrow) ftattn_ctx();
+  if (!c) return fail(nullptr, FTATTN_ENOMEM, "out of host memory");
+  c->cfg = *cfg;
+  ftattn_config& e = c->cfg;
+  e.stride = 8;
+  e.block_n = BN;
+  if (!(e.softmax_scale > 0.f)) e.softmax_scale = 1.0f / std::sqrt((float)e.head_dim);
+  if (!(e.eps1 > 0.f)) e.eps1 = 0.03f;
+  if (!(e.tau_o > 0.f)) e.tau_o = 0.75f / 512.0f;
+  if (!(e.delta_l > 0.f)) e.delta_l = 1.0f / 1024.0f;
+  if (e.max_events <= 0) e.max_events = 65536;
+  c->BH = e.batch * e.heads;
+  c->Tj = (e.seq + BN - 1) / BN;
+  if (e.block_m == 0) {
+    e.block_m = 128;
+  }
+  c->BM = e.block_m;
+  c->NW = 4;
+  c->NQ = c->BM / 128;
+  c->Ti = (e.seq + c->BM - 1) / c->BM;
+
+  hipError_t he = hipSetDevice(e.device);
+  if (he != hipSuccess) { int rc = fail(nullptr, FTATTN_EHIP, std::string("hipSetDevice: ") + hipGetErrorString(he)); delete c; return rc; }
+
+  const int D = e.head_dim;
+  size_t n_kc = (size_t)c->BH * c->Tj * (BN + CKR) * D;
+  size_t n_vt = (size_t)c->BH * c->Tj * (D + CKR) * BN;
+  size_t n_q = (size_t)c->BH * e.seq * D;
+  c->fault_cap = 1 << 16;
+#define CREATE_TRY(expr)                                                                                  \
+  do {                                                                                                    \
+    hipError_t e_ = (expr);                                                                               \
+    if (e_ != hipSuccess) {                                                                               \
+      int rc_ = fail(nullptr, e_ == hipErrorOutOfMemory ? FTATTN_ENOMEM : FTATTN_EHIP,                    \
+                     std::string(#expr) + ": " + hipGetErrorString(e_));                                  \
+      release(c);                                                                                         \
+      return rc_;                                                                                         \
+    }                                                                                                     \
+  } while (0)
+  if (e.in_dtype == FTATTN_BF16) CREATE_TRY(hipMalloc((void**)&c->qh, n_q * 2));
+  CREATE_TRY(hipMalloc((void**)&c->kc, n_kc * 2));
+  CREATE_TRY(hipMalloc((void**)&c->vt, n_vt * 2));
+  CREATE_TRY(hipMalloc((void**)&c->d_faults, sizeof(DevFault) * c->fault_cap));
+  CREATE_TRY(hipMalloc((void**)&c->d_fault_off, sizeof(int32_t) * ((size_t)c->BH * c->Ti + 1)));
+  CREATE_TRY(hipMalloc((void**)&c->d_events, sizeof(ftattn_event) * (size_t)e.max_events));
+  CREATE_TRY(hipMalloc((void**)&c->d_ev_count, sizeof(int32_t)));
+  CREATE_TRY(hipMalloc((void**)&c->d_recheck, sizeof(unsigned long long)));
+  CREATE_TRY(hipMalloc((void**)&c->d_resmax, sizeof(uint32_t) * (size_t)c->BH * c->Ti * 4));
+  CREATE_TRY(hipHostMalloc((void**)&c->h_faults, sizeof(DevFault) * c->fault_cap, hipHostMallocDefault));
+  CREATE_TRY(hipHostMalloc((void**)&c->h_fault_off, sizeof(int32_t) * ((size_t)c->BH * c->Ti + 1), hipHostMallocDefault));
+  // the checksum rows of the encoded tiles are never written when ft_mode is OFF; keep them defined
+  CREATE_TRY(hipMemset(c->kc, 0, n_kc * 2));
+  CREATE_TRY(hipMemset(c->vt, 0, n_vt * 2));
+  CREATE_TRY(hipMemset(c->d_ev_count, 0, sizeof(int32_t)));
+  CREATE_TRY(hipMemset(c->d_recheck, 0, sizeof(unsigned long long)));
+  CREATE_TRY(hipMemset(c->d_resmax, 0, sizeof(uint32_t) * (size_t)c->BH * c->Ti * 4));
+  for (int ft = 0; ft < 2; ++ft)
+    for (int ca = 0; ca < 2; ++ca) {
+      main_fn f = select_kernel(D, c->NW, c->NQ, ft != 0, ca != 0);
+      if (!f) { release(c); return fail(nullptr, FTATTN_EUNSUPPORTED, "no kernel for this tile shape"); }
+      CREATE_TRY(hipFuncSetAttribute((const void*)f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes(D)));
+    }
+  CREATE_TRY(hipDeviceSynchronize());
+#undef CREATE_TRY
+  *out = c;
+  return FTATTN_OK;
+}
+
+extern "C" int ftattn_get_config(const ftattn_ctx* ctx, ftattn_config* effective) {
+  if (!ctx || !effective) return FTATTN_EINVAL;
+  *effective = ctx->cfg;
+  return FTATTN_OK;
+}
+
+static int n_tiles_for_row(const ftattn_config& e, int row) {
+  int last_key = e.causal ? row : e.seq - 1;
+  return last_key / BN + 1;
+}
+
+extern "C" int ftattn_forward(ftattn_ctx* c, const void* q, const void* k, const void* v, void* o,
+                              const ftattn_fault* faults, int32_t n_faults, void* hip_stream) {
+  if (!c) return FTATTN_EINVAL;
+  if (!q || !k || !v || !o) return fail(c, FTATTN_EINVAL, "null tensor pointer");
+  if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o) & 15) return fail(c, FTATTN_EINVAL, "tensor pointers must be 16-byte aligned");
+  if (n_faults < 0 || (n_faults > 0 && !faults)) return fail(c, FTATTN_EINVAL, "bad fault list");
+  if (n_faults > c->fault_cap) return fail(c, FTATTN_EINVAL, "too many faults (limit 65536)");
+  const ftattn_config& e = c->cfg;
+  const int D = e.head_dim, N = e.seq;
+  hipStream_t st = (hipStream_t)hip_stream;
+  HIP_TRY(c, hipSetDevice(e.device));
+
+  // ---- validate and bucket the fault list by (head, row tile), ordered by key tile
+  if (n_faults > 0) {
+    struct Keyed { long long key; DevFault f; };
+    std::vector<Keyed> ks(n_faults);
+    for (int i = 0; i < n_faults; ++i) {
+      const ftattn_fault& f = faults[i];
+      char msg[160];
+      bool ok = f.b >= 0 && f.b < e.batch && f.h >= 0 && f.h < e.heads && f.row >= 0 && f.row < N && f.bit >= 0 && f.bit <= 31 &&
+                f.stage >= FTATTN_ST_S && f.stage <= FTATTN_ST_OACC && f.kv_tile >= 0 && f.kv_tile < n_tiles_for_row(e, f.row);
+      if (ok && (f.stage == FTATTN_ST_S || f.stage == FTATTN_ST_EXP))
+        ok = f.col >= 0 && f.col < N && (!e.causal || f.col <= f.row) && f.kv_tile == f.col / BN;
+      if (ok && f.stage == FTATTN_ST_OACC) ok = f.col >= 0 && f.col < D;
+      if (!ok) {
+        snprintf(msg, sizeof msg, "fault %d (b=%d h=%d stage=%d kv_tile=%d row=%d col=%d bit=%d) names a masked or out-of-range position",
+                 i, f.b, f.h, f.stage, f.kv_tile, f.row, f.col, f.bit);
+        return fail(c, FTATTN_EINVAL, msg);
+      }
+      long long bucket = (long long)(f.b * e.heads + f.h) * c->Ti + f.row / c->BM;
+      ks[i].key = (bucket << 32) | ((long long)f.kv_tile << 8) | f.stage;
+      ks[i].f = DevFault{f.stage, f.kv_tile, f.row, f.col, f.bit};
+    }
+    std::stable_sort(ks.begin(), ks.end(), [](const Keyed& a, const Keyed& b) { return a.key < b.key; });
+    size_t nb = (size_t)c->BH * c->Ti;
+    std::fill(c->h_fault_off, c->h_fault_off + nb + 1, 0);
+    for (int i = 0; i < n_faults; ++i) { c->h_faults[i] = ks[i].f; c->h_fault_off[(ks[i].key >> 32) + 1]++; }
+    for (size_t i = 0; i < nb; ++i) c->h_fault_off[i + 1] += c->h_fault_off[i];
+    HIP_TRY(c, hipMemcpyAsync(c->d_faults, c->h_faults, sizeof(DevFault) * n_faults, hipMemcpyHostToDevice, st));
+    HIP_TRY(c, hipMemcpyAsync(c->d_fault_off, c->h_fault_off, sizeof(int32_t) * (nb + 1), hipMemcpyHostToDevice, st));
+    HIP_TRY(c, hipStreamSynchronize(st));   // the staging buffers may be rewritten by the next call
+  }
+
+  const bool ft = e.ft_mode != FTATTN_FT_OFF;
+  int n_resmax = c->BH * c->Ti * 4;
+  ftattn_reset<<<(n_resmax + 255) / 256, 256, 0, st>>>(c->d_ev_count, c->d_recheck, c->d_resmax, n_resmax);
+
+  // ---- encode (Algorithm 1: "Encode tensor checksum"), once per key tile for all row tiles
+  const _Float16* qh = (const _Float16*)q;
+  if (e.in_dtype == FTATTN_BF16) {
+    size_t n = (size_t)c->BH * N * D;
+    ftattn_convert_q<<<(unsigned)((n / 8 + 255) / 256 + 1), 256, 0, st>>>((const uint16_t*)q, c->qh, n);
+    qh = c->qh;
+  }
+  dim3 eg(c->Tj, c->BH);
+  if (D == 128) {
+    ftattn_encode_k<128><<<eg, 256, 0, st>>>(k, e.in_dtype, c->kc, N, c->Tj, ft ? 1 : 0);
+    ftattn_encode_v<128><<<eg, 256, 0, st>>>(v, e.in_dtype, c->vt, N, c->Tj, ft ? 1 : 0);
+  } else {
+    ftattn_encode_k<64><<<eg, 256, 0, st>>>(k, e.in_dtype, c->kc, N, c->Tj, ft ? 1 : 0);
+    ftattn_encode_v<64><<<eg, 256, 0, st>>>(v, e.in_dtype, c->vt, N, c->Tj, ft ? 1 : 0);
+  }
+
+  // ---- the fused pass
+  KArgs a;
+  a.q = qh; a.kc = c->kc; a.vt = c->vt; a.o = o; a.out_dtype = e.out_dtype;
+  a.N = N; a.H = e.heads; a.Ti = c->Ti; a.Tj = c->Tj;
+  a.scale = e.softmax_scale;
+  a.scale_log2 = e.softmax_scale * 1.4426950408889634f;
+  a.eps1 = e.eps1;
+  a.tau_fast = 0.5f * (1.0f - std::exp(-e.eps1));
+  a.tau_o = e.tau_o; a.delta_l = e.delta_l;
+  a.correct = e.ft_mode == FTATTN_FT_CORRECT ? 1 : 0;
+  a.faults = c->d_faults;
+  a.fault_off = n_faults > 0 ? c->d_fault_off : nullptr;
+  a.events = c->d_events; a.ev_count = c->d_ev_count; a.max_events = e.max_events;
+  a.resmax = c->d_resmax; a.recheck = c->d_recheck;
+  main_fn f = select_kernel(D, c->NW, c->NQ, ft, e.causal != 0);
+  hipLaunchKernelGGL(f, dim3(c->BH * c->Ti), dim3(c->NW * 64), lds_bytes(D), st, a);
+  HIP_TRY(c, hipGetLastError());
+  c->last_stream = st;
+  c->ran = true;
+  return FTATTN_OK;
+}
+
+extern "C" int ftattn_report(ftattn_ctx* c, ftattn_report_view* out) {
+  if (!c || !out) return FTATTN_EINVAL;
+  if (!c->ran) return fail(c, FTATTN_EINVAL, "no forward call to report on");
+  const ftattn_config& e = c->cfg;
+  HIP_TRY(c, hipSetDevice(e.device));
+  HIP_TRY(c, hipStreamSynchronize(c->last_stream));
+  int32_t count = 0;
+  unsigned long long recheck = 0;
+  HIP_TRY(c, hipMemcpy(&count, c->d_ev_count, sizeof count, hipMemcpyDeviceToHost));
+  HIP_TRY(c, hipMemcpy(&recheck, c->d_recheck, sizeof recheck, hipMemcpyDeviceToHost));
+  int stored = std::min(count, e.max_events);
+  c->events.resize(stored);
+  if (stored) HIP_TRY(c, hipMemcpy(c->events.data(), c->d_events, sizeof(ftattn_event) * stored, hipMemcpyDeviceToHost));
+  std::sort(c->events.begin(), c->events.end(), [](const ftattn_event& x, const ftattn_event& y) {
+    if (x.b != y.b) return x.b < y.b;
+    if (x.h != y.h) return x.h < y.h;
+    if (x.check != y.check) return x.check < y.check;
+    if (x.kv_tile != y.kv_tile) return x.kv_tile < y.kv_tile;
+    if (x.row != y.row) return x.row < y.row;
+    return x.col < y.col;
+  });
+  size_t n_rt = (size_t)c->BH * c->Ti;
+  c->tile_flags.assign(n_rt * c->Tj, 0);
+  c->rowtile_flags.assign(n_rt, 0);
+  for (const ftattn_event& ev : c->events) {
+    size_t rt = (size_t)(ev.b * e.heads + ev.h) * c->Ti + ev.row / c->BM;
+    if (ev.check == FTATTN_CHECK_S) c->tile_flags[rt * c->Tj + ev.kv_tile] |= FTATTN_TF_DET_S | (ev.action ? FTATTN_TF_COR_S : 0);
+    else if (ev.check == FTATTN_CHECK_EXP) c->tile_flags[rt * c->Tj + ev.kv_tile] |= FTATTN_TF_DET_EXP | (ev.action ? FTATTN_TF_COR_EXP : 0);
+    else if (ev.check == FTATTN_CHECK_L) c->rowtile_flags[rt] |= FTATTN_RF_DET_L | (ev.action ? FTATTN_RF_COR_L : 0);
+    else c->rowtile_flags[rt] |= FTATTN_RF_DET_O | (ev.action ? FTATTN_RF_COR_O : 0);
+  }
+  if (count > stored)
+    for (auto& f : c->rowtile_flags) f |= FTATTN_RF_EVENT_OVERFLOW;
+  c->resmax.resize(n_rt * 4);
+  HIP_TRY(c, hipMemcpy(c->resmax.data(), c->d_resmax, sizeof(float) * n_rt * 4, hipMemcpyDeviceToHost));
+  out->n_events = stored;
+  out->n_events_dropped = count - stored;
+  out->events = c->events.data();
+  out->tiles_m = c->Ti;
+  out->tiles_n = c->Tj;
+  out->tile_flags = c->tile_flags.data();
+  out->rowtile_flags = c->rowtile_flags.data();
+  out->residual_max = c->resmax.data();
+  out->recheck_entries = (int64_t)recheck;
+  return FTATTN_OK;
+}
+
+extern "C" int ftattn_destroy(ftattn_ctx* c) {
+  if (!c) return FTATTN_EINVAL;
+  (void)hipSetDevice(c->cfg.device);
+  (void)hipDeviceSynchronize();
+  release(c);
+  return FTATTN_OK;
+}
+
+extern "C" const char* ftattn_last_error(const ftattn_ctx* c) {
+  return c ? c->err.c_str() : g_create_err.c_str();
+}

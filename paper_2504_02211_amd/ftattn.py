@@ -1,0 +1,163 @@
+"""Thin ctypes binding of libftattn.so: argument marshalling only.
+
+Every step of the attention pass runs inside the HIP library; this module passes
+device pointers of torch tensors and copies the host-side report into numpy
+arrays.  It raises if the library has not been built -- there is no fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libftattn.so")
+
+F16, BF16, F32 = 0, 1, 2
+ST_S, ST_EXP, ST_ROWSUM, ST_OACC = 0, 1, 2, 3
+CHECK_S, CHECK_EXP, CHECK_L, CHECK_O = 0, 1, 2, 3
+FT_OFF, FT_CORRECT, FT_DETECT = 0, 1, 2
+OK, EINVAL, EUNSUPPORTED, EHIP, ENOMEM = 0, -1, -2, -3, -4
+
+EXPORTS = ("ftattn_create", "ftattn_get_config", "ftattn_forward", "ftattn_report", "ftattn_destroy",
+           "ftattn_last_error")
+
+
+class Config(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("batch", C.c_int32), ("heads", C.c_int32), ("seq", C.c_int32),
+                ("head_dim", C.c_int32), ("in_dtype", C.c_int32), ("out_dtype", C.c_int32), ("causal", C.c_int32),
+                ("softmax_scale", C.c_float), ("ft_mode", C.c_int32), ("stride", C.c_int32), ("block_m", C.c_int32),
+                ("block_n", C.c_int32), ("eps1", C.c_float), ("tau_o", C.c_float), ("delta_l", C.c_float),
+                ("max_events", C.c_int32), ("device", C.c_int32)]
+
+
+class Fault(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("b", "h", "stage", "kv_tile", "row", "col", "bit")]
+
+
+class Event(C.Structure):
+    _fields_ = [("b", C.c_int32), ("h", C.c_int32), ("check", C.c_int32), ("kv_tile", C.c_int32), ("row", C.c_int32),
+                ("col", C.c_int32), ("residual", C.c_float), ("action", C.c_int32)]
+
+
+class ReportView(C.Structure):
+    _fields_ = [("n_events", C.c_int32), ("n_events_dropped", C.c_int32), ("events", C.POINTER(Event)),
+                ("tiles_m", C.c_int32), ("tiles_n", C.c_int32), ("tile_flags", C.POINTER(C.c_uint8)),
+                ("rowtile_flags", C.POINTER(C.c_uint8)), ("residual_max", C.POINTER(C.c_float)),
+                ("recheck_entries", C.c_int64)]
+
+
+EVENT_DTYPE = np.dtype([("b", "<i4"), ("h", "<i4"), ("check", "<i4"), ("kv_tile", "<i4"), ("row", "<i4"),
+                        ("col", "<i4"), ("residual", "<f4"), ("action", "<i4")])
+
+_lib = None
+
+
+class FtAttnError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"ftattn error {code}: {msg}")
+        self.code = code
+
+
+def load_library() -> C.CDLL:
+    """Loads the built library; raises if it is missing (no CPU fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} is not built; run `python -m paper_2504_02211_amd.build`")
+    lib = C.CDLL(LIB_PATH)
+    lib.ftattn_create.argtypes = [C.POINTER(Config), C.POINTER(C.c_void_p)]
+    lib.ftattn_get_config.argtypes = [C.c_void_p, C.POINTER(Config)]
+    lib.ftattn_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(Fault),
+                                   C.c_int32, C.c_void_p]
+    lib.ftattn_report.argtypes = [C.c_void_p, C.POINTER(ReportView)]
+    lib.ftattn_destroy.argtypes = [C.c_void_p]
+    lib.ftattn_last_error.argtypes = [C.c_void_p]
+    lib.ftattn_last_error.restype = C.c_char_p
+    for n in ("ftattn_create", "ftattn_get_config", "ftattn_forward", "ftattn_report", "ftattn_destroy"):
+        getattr(lib, n).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+class Report:
+    """Host copy of ftattn_report's view."""
+
+    def __init__(self, view: ReportView, batch: int, heads: int):
+        n = view.n_events
+        self.n_events = n
+        self.n_events_dropped = view.n_events_dropped
+        self.tiles_m, self.tiles_n = view.tiles_m, view.tiles_n
+        if n:
+            buf = C.string_at(view.events, n * C.sizeof(Event))
+            self.events = np.frombuffer(buf, dtype=EVENT_DTYPE).copy()
+        else:
+            self.events = np.zeros(0, dtype=EVENT_DTYPE)
+        nrt = batch * heads * view.tiles_m
+        self.tile_flags = np.ctypeslib.as_array(view.tile_flags, shape=(nrt * view.tiles_n,)).copy().reshape(
+            batch, heads, view.tiles_m, view.tiles_n)
+        self.rowtile_flags = np.ctypeslib.as_array(view.rowtile_flags, shape=(nrt,)).copy().reshape(
+            batch, heads, view.tiles_m)
+        self.residual_max = np.ctypeslib.as_array(view.residual_max, shape=(nrt * 4,)).copy().reshape(
+            batch, heads, view.tiles_m, 4)
+        self.recheck_entries = int(view.recheck_entries)
+
+    def event_set(self):
+        """Set of (b, h, check, kv_tile, row, col) tuples."""
+        e = self.events
+        return set(zip(e["b"].tolist(), e["h"].tolist(), e["check"].tolist(), e["kv_tile"].tolist(),
+                       e["row"].tolist(), e["col"].tolist()))
+
+
+class FtAttn:
+    """One context of the C library (one shape, one device)."""
+
+    def __init__(self, batch: int, heads: int, seq: int, head_dim: int, in_dtype: int, causal: bool,
+                 out_dtype: int = F32, ft_mode: int = FT_CORRECT, softmax_scale: float = 0.0, block_m: int = 0,
+                 eps1: float = 0.0, tau_o: float = 0.0, delta_l: float = 0.0, max_events: int = 0, device: int = 0):
+        self.lib = load_library()
+        cfg = Config(C.sizeof(Config), batch, heads, seq, head_dim, in_dtype, out_dtype, int(bool(causal)),
+                     softmax_scale, ft_mode, 8, block_m, 0, eps1, tau_o, delta_l, max_events, device)
+        self.handle = C.c_void_p()
+        rc = self.lib.ftattn_create(C.byref(cfg), C.byref(self.handle))
+        if rc != OK:
+            self.handle = C.c_void_p()
+            raise FtAttnError(rc, self.lib.ftattn_last_error(None).decode())
+        eff = Config()
+        self.lib.ftattn_get_config(self.handle, C.byref(eff))
+        self.config = eff
+
+    def forward(self, q, k, v, o, faults: Optional[np.ndarray] = None, stream: int = 0) -> None:
+        """q, k, v, o: objects with data_ptr() (torch device tensors) or integer device addresses.
+        faults: int32 array [n, 7] of (b, h, stage, kv_tile, row, col, bit)."""
+        ptr = lambda t: C.c_void_p(t if isinstance(t, int) else t.data_ptr())
+        n = 0
+        fp = None
+        if faults is not None and len(faults):
+            fa = np.ascontiguousarray(faults, dtype=np.int32).reshape(-1, 7)
+            n = fa.shape[0]
+            fp = fa.ctypes.data_as(C.POINTER(Fault))
+        rc = self.lib.ftattn_forward(self.handle, ptr(q), ptr(k), ptr(v), ptr(o), fp, n, C.c_void_p(stream))
+        if rc != OK:
+            raise FtAttnError(rc, self.lib.ftattn_last_error(self.handle).decode())
+
+    def report(self) -> Report:
+        view = ReportView()
+        rc = self.lib.ftattn_report(self.handle, C.byref(view))
+        if rc != OK:
+            raise FtAttnError(rc, self.lib.ftattn_last_error(self.handle).decode())
+        return Report(view, self.config.batch, self.config.heads)
+
+    def close(self) -> None:
+        if self.handle:
+            self.lib.ftattn_destroy(self.handle)
+            self.handle = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
