@@ -358,7 +358,7 @@ __global__ __launch_bounds__(NW * 64) void ftattn_main(const KArgs a) {
               pr *= ((p[1][r] * p[1][4 + r]) * s2) * ((p[1][8 + r] * p[1][12 + r]) * s2);
               float dv = __builtin_fabsf(pr - 1.0f);
               bad |= !(dv <= a.tau_fast);
-              dev_max = fmax2(dev_max, dv);
+              dev_max = fmax2(dev_max, dv <= a.tau_fast ? dv : 0.f);   // largest deviation that passed
             }
             recheck = wave_any(bad);
             if (recheck) ++rechecks;
@@ -447,7 +447,9 @@ __global__ __launch_bounds__(NW * 64) void ftattn_main(const KArgs a) {
               }
             }
             // a repaired score changes the row's maximum and exponentials: recompute the row
-            bool redo = lin_fixed || (xchg32(lin_fixed ? 1.f : 0.f, hi) != 0.f);
+            // (the exchange is a wave-wide operation: evaluate it outside any per-lane short circuit)
+            const float partner_fixed = xchg32(lin_fixed ? 1.f : 0.f, hi);
+            bool redo = lin_fixed | (partner_fixed != 0.f);
             if (wave_any(redo)) {
               float mx2 = -__builtin_inff();
 #pragma unroll
