@@ -47,7 +47,9 @@ listed in the design notes of the repository):
   ("correct EXP with recomputation").
 * Restoring an element is done by reconstruction (checksum minus the other
   folds), which equals "adding the residual" algebraically but never reuses a
-  corrupted, possibly infinite, value.
+  corrupted, possibly infinite, value.  When the residual ratio is not finite
+  (an Inf/NaN result, or residuals beyond the floating-point range) the located
+  fold is the one of largest magnitude, if it is unique.
 * The lower bound of the row-sum uses the *local* maximum of each key tile,
   carried with the same rescale as the row-sum; the upper bound is the number
   of unmasked keys of the row; both get a relative slack delta_l and equality is
@@ -171,9 +173,12 @@ def locate_and_restore(x: np.ndarray, chk1: float, chk2: float) -> Tuple[int, fl
         if 0 <= cand < n:
             lstar = cand
     else:
-        bad = np.flatnonzero(~np.isfinite(x))
-        if bad.size == 1:
-            lstar = int(bad[0])
+        # residuals not finite: the fold of overwhelming size (a non-finite value counts as
+        # largest); two folds of equal size cannot be told apart
+        mag = np.where(np.isfinite(x), np.abs(x), np.inf)
+        top = np.flatnonzero(mag == mag.max())
+        if top.size == 1:
+            lstar = int(top[0])
     if lstar < 0:
         return -1, 0.0
     rest = np.delete(x, lstar).sum()

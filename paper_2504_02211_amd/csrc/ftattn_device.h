@@ -394,23 +394,24 @@ __global__ __launch_bounds__(NW * 64) void ftattn_main(const KArgs a) {
                 bool linear = !(a.scale * __builtin_fabsf(R1) <= 0.5f * a.eps1);
                 if (linear) {
                   float chk2 = sc[g][8 + r] + sc[g][12 + r];
-                  float sum2 = 0.f;
-                  int n_nonfin = 0, l_nonfin = -1;
+                  float sum2 = 0.f, big = -1.f;
+                  int l_big = -1;
 #pragma unroll
                   for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                     for (int gg = 0; gg < 4; ++gg) {
                       float sv = s[g][kb][4 * gg + r];
                       sum2 += (float)(4 * kb + gg + 1) * sv;
-                      if (!finitef(sv)) { ++n_nonfin; l_nonfin = 4 * kb + gg; }
+                      float mag = finitef(sv) ? __builtin_fabsf(sv) : __builtin_inff();
+                      if (mag > big) { big = mag; l_big = 4 * kb + gg; } else if (mag == big) { l_big = -1; }
                     }
                   float ratio = (chk2 - sum2) / R1;
                   int lstar = -1;
                   if (finitef(ratio)) {
                     float c = __builtin_rintf(ratio) - 1.0f;
                     if (c >= 0.f && c < (float)NFOLD_K) lstar = (int)c;
-                  } else if (n_nonfin == 1) {
-                    lstar = l_nonfin;
+                  } else {
+                    lstar = l_big;   // residuals left the fp32 range: the fold of overwhelming size
                   }
                   int col = lstar >= 0 ? k0 + 32 * (lstar >> 2) + 8 * (lstar & 3) + 4 * hi + r : -1;
                   bool fix = a.correct && lstar >= 0;
@@ -601,23 +602,24 @@ __global__ __launch_bounds__(NW * 64) void ftattn_main(const KArgs a) {
         for (int r = 0; r < 4; ++r) {
           if (real && !(__builtin_fabsf(R[r]) <= a.tau_o)) {
             float chk1 = oc[g][r] + oc[g][4 + r], chk2 = oc[g][8 + r] + oc[g][12 + r];
-            float sum2 = 0.f;
-            int n_nonfin = 0, l_nonfin = -1;
+            float sum2 = 0.f, big = -1.f;
+            int l_big = -1;
 #pragma unroll
             for (int fb = 0; fb < NFB; ++fb)
 #pragma unroll
               for (int gg = 0; gg < 4; ++gg) {
                 float ov = o[g][fb][4 * gg + r];
                 sum2 += (float)(4 * fb + gg + 1) * ov;
-                if (!finitef(ov)) { ++n_nonfin; l_nonfin = 4 * fb + gg; }
+                float mag = finitef(ov) ? __builtin_fabsf(ov) : __builtin_inff();
+                if (mag > big) { big = mag; l_big = 4 * fb + gg; } else if (mag == big) { l_big = -1; }
               }
             float ratio = (chk2 - sum2) / R[r];
             int lstar = -1;
             if (finitef(ratio)) {
               float c = __builtin_rintf(ratio) - 1.0f;
               if (c >= 0.f && c < (float)NFOLD_V) lstar = (int)c;
-            } else if (n_nonfin == 1) {
-              lstar = l_nonfin;
+            } else {
+              lstar = l_big;
             }
             int col = lstar >= 0 ? 8 * lstar + 4 * hi + r : -1;
             bool fix = a.correct && lstar >= 0;

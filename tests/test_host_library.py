@@ -1,0 +1,96 @@
+"""CPU-only checks of the host side: the library loads, exports what the header declares, and
+rejects bad configurations before touching a device.  Also covers the synthetic-input module."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2504_02211_amd import ftattn, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "ftattn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ftattn_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ftattn.load_library()
+    names = _declared_functions()
+    assert set(names) == set(ftattn.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_struct_layouts_match_header():
+    assert C.sizeof(ftattn.Config) == 18 * 4
+    assert C.sizeof(ftattn.Fault) == 7 * 4
+    assert C.sizeof(ftattn.Event) == 8 * 4 == ftattn.EVENT_DTYPE.itemsize
+
+
+def test_create_rejects_bad_configs_without_a_device():
+    lib = ftattn.load_library()
+    def create(**kw):
+        base = dict(struct_size=C.sizeof(ftattn.Config), batch=1, heads=1, seq=128, head_dim=64, in_dtype=0, out_dtype=2,
+                    causal=0, softmax_scale=0.0, ft_mode=1, stride=8, block_m=0, block_n=0, eps1=0.0, tau_o=0.0,
+                    delta_l=0.0, max_events=0, device=0)
+        base.update(kw)
+        cfg = ftattn.Config(**base)
+        h = C.c_void_p()
+        rc = lib.ftattn_create(C.byref(cfg), C.byref(h))
+        return rc, lib.ftattn_last_error(None).decode()
+    assert create(struct_size=12)[0] == ftattn.EINVAL
+    assert create(head_dim=80)[0] == ftattn.EUNSUPPORTED
+    assert create(seq=0)[0] == ftattn.EINVAL
+    assert create(in_dtype=2)[0] == ftattn.EINVAL
+    assert create(out_dtype=1)[0] == ftattn.EINVAL          # bf16 out for fp16 in
+    assert create(stride=4)[0] == ftattn.EUNSUPPORTED
+    assert create(block_n=128)[0] == ftattn.EUNSUPPORTED
+    assert create(ft_mode=5)[0] == ftattn.EINVAL
+    rc, msg = create(block_m=96)
+    assert rc == ftattn.EUNSUPPORTED and "block_m" in msg
+    assert lib.ftattn_forward(None, None, None, None, None, None, 0, None) == ftattn.EINVAL
+    assert lib.ftattn_report(None, None) == ftattn.EINVAL
+    assert lib.ftattn_destroy(None) == ftattn.EINVAL
+
+
+def test_synth_is_deterministic_and_exact():
+    q1, k1, v1 = synth.gen_workload(1)
+    q2, k2, v2 = synth.gen_workload(1)
+    assert np.array_equal(q1, q2) and np.array_equal(k1, k2) and np.array_equal(v1, v2)
+    x = synth.bits_to_f64(q1, synth.F16)
+    assert abs(x.mean()) < 0.05 and abs(x.std() - 1) < 0.05
+    # bf16 round trip and round-to-nearest-even
+    vals = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, -3.1415926, 65280.0], np.float32)
+    bits = synth.f32_to_bf16_bits(vals)
+    back = synth.bf16_bits_to_f64(bits)
+    assert back[0] == 1.0 and back[1] == 1.0 and back[2] == 1.0 + 2.0 ** -6 and back[4] == 65280.0
+    assert abs(back[3] + 3.1415926) < 2.0 ** -7
+    # a subset of heads reproduces the same bits; outlier rows are scaled
+    qa, ka, va = synth.gen_workload(4, heads_subset=[(1, 3)])
+    qb, kb, vb = synth.gen_workload(4, heads_subset=[(0, 0), (1, 3)])
+    assert np.array_equal(ka[1, 3], kb[1, 3]) and not ka[0, 0].any()
+    kk = synth.bits_to_f64(ka[1, 3], synth.BF16)
+    assert (np.abs(kk).max(axis=1) > 12).sum() >= 30
+
+
+def test_candidate_streams_respect_the_mask_and_the_seu_rule():
+    w = synth.WORKLOADS[3]
+    s = synth.candidate_stream(1, 0, 0, 0, w.seq, w.head_dim, 64, True, (synth.ST_S, synth.ST_EXP, synth.ST_ROWSUM, synth.ST_OACC), 20, 30)
+    seen = [next(s) for _ in range(500)]
+    for (b, h, st, kt, row, col, bit) in seen:
+        assert 20 <= bit <= 30 and 0 <= row < w.seq and kt < synth.n_kv_tiles(row, w.seq, 64, True)
+        if st in (synth.ST_S, synth.ST_EXP):
+            assert col <= row and kt == col // 64
+        if st == synth.ST_OACC:
+            assert 0 <= col < w.head_dim
+    s2 = synth.candidate_stream(1, 0, 0, 0, w.seq, w.head_dim, 64, True, (synth.ST_S, synth.ST_EXP, synth.ST_ROWSUM, synth.ST_OACC), 20, 30)
+    assert [next(s2) for _ in range(500)] == seen
+    assert synth.conflicts((0, 0, synth.ST_EXP, 1, 5, 70, 3), [(0, 0, synth.ST_S, 1, 5, 90, 4)])
+    assert not synth.conflicts((0, 0, synth.ST_EXP, 2, 5, 130, 3), [(0, 0, synth.ST_S, 1, 5, 90, 4)])
+    assert synth.conflicts((0, 0, synth.ST_OACC, 2, 5, 11, 3), [(0, 0, synth.ST_OACC, 0, 5, 3, 4)])
+    assert len(list(synth.workload_fault_slots(4))) == 4 * 32 * 4
