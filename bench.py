@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Throughput of the fused fault-tolerant attention pass on one MI355X.
+
+A step is one ftattn_forward call: encode (tensor checksums, operand conversion and transposition)
+plus the fused kernel, on synthetic inputs of the long-sequence workload (batch 1, 32 heads,
+16384 tokens, head_dim 128, bf16, causal) that are resident in HBM before the timed region.
+Prints one JSON line: FT throughput (value), the unprotected twin, the overhead, the roofline of
+the fused kernel from HIP events recorded on the launch stream, and the CPU oracle timed on a
+bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_PEAK_TFLOPS = 2500.0     # MI355X dense fp16 / bf16 MFMA, published
+
+
+def useful_flops(w) -> float:
+    """4*d flop per unmasked score element (2*d in each GEMM); checksum work is not counted."""
+    n = w.seq * (w.seq + 1) // 2 if w.causal else w.seq * w.seq
+    return 4.0 * w.head_dim * n * w.batch * w.heads
+
+
+def time_variant(torch, ftattn, w, tq, tk, tv, ft_mode, steps, warmup, block_m):
+    o = torch.empty((w.batch, w.heads, w.seq, w.head_dim), dtype=torch.float32, device="cuda")
+    ctx = ftattn.FtAttn(w.batch, w.heads, w.seq, w.head_dim, w.dtype, w.causal, ft_mode=ft_mode, block_m=block_m)
+    stream = torch.cuda.Stream()
+    sp = stream.cuda_stream
+    for _ in range(warmup):
+        ctx.forward(tq, tk, tv, o, None, sp)
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(stream):
+        e0.record(stream)
+        for _ in range(steps):
+            ctx.forward(tq, tk, tv, o, None, sp)
+        e1.record(stream)
+    torch.cuda.synchronize()
+    ms_step = e0.elapsed_time(e1) / steps
+    # per-kernel durations from HIP events the library records on the same stream
+    ctx.set_timing(True)
+    enc, main = [], []
+    for _ in range(min(steps, 10)):
+        ctx.forward(tq, tk, tv, o, None, sp)
+        a, b = ctx.get_timing()
+        enc.append(a); main.append(b)
+    ctx.set_timing(False)
+    rep = ctx.report()
+    info = dict(ms_step=ms_step, ms_encode=sum(enc) / len(enc), ms_main=sum(main) / len(main), events=rep.n_events,
+                rechecks=rep.recheck_entries, block_m=ctx.config.block_m, block_n=ctx.config.block_n)
+    ctx.close()
+    return info
+
+
+def cpu_baseline(w, q, k, v, n_heads=4):
+    """The fp64 oracle (definition + Algorithm 1) on every query row of the first heads."""
+    import numpy as np
+    from oracle import efta_oracle as orc
+    from paper_2504_02211_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    prm = orc.Params(scale=float(w.head_dim) ** -0.5, causal=w.causal, block_n=64)
+    rows = np.arange(w.seq)
+    n_heads = min(n_heads, w.heads)
+    dt = 0.0
+    for h in range(n_heads):
+        Q, K, V = (synth.bits_to_f64(x[0, h], w.dtype) for x in (q, k, v))
+        t0 = time.perf_counter()
+        orc.attention_clean(Q, K, V, prm.scale, prm.causal, rows)
+        orc.efta_rows(Q, rows, K, V, prm)
+        dt += time.perf_counter() - t0
+    cnt = float(((rows + 1) if w.causal else np.full(w.seq, w.seq)).sum()) * n_heads
+    flops = 4.0 * w.head_dim * cnt              # useful flops of ONE attention pass over the sample
+    return {"value": round(flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"all {w.seq} query rows of heads (0,0..{n_heads - 1}) of workload {w.cfg}: definition + "
+                      f"Algorithm 1 in fp64, {dt:.1f} s; rate counts one pass of useful flops"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", type=int, default=5)
+    ap.add_argument("--block-m", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--all-workloads", action="store_true", help="also time workloads 2-4 (extra keys)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(the path shards over batch*heads and row tiles without communication, see DESIGN.md)", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2504_02211_amd import ftattn, synth
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+    def to_dev(bits, dtype):
+        import numpy as np
+        t = torch.from_numpy(bits.view(np.int16)).cuda()
+        return t.view(torch.float16 if dtype == synth.F16 else torch.bfloat16)
+
+    results = {}
+    keep = None
+    for cfg in ([args.workload] + ([c for c in (2, 3, 4) if c != args.workload] if args.all_workloads else [])):
+        w = synth.WORKLOADS[cfg]
+        q, k, v = synth.gen_workload(cfg)
+        tq, tk, tv = (to_dev(x, w.dtype) for x in (q, k, v))
+        ft = time_variant(torch, ftattn, w, tq, tk, tv, ftattn.FT_CORRECT, args.steps, args.warmup, args.block_m)
+        un = time_variant(torch, ftattn, w, tq, tk, tv, ftattn.FT_OFF, args.steps, args.warmup, args.block_m)
+        results[cfg] = (w, ft, un)
+        if cfg == args.workload:
+            keep = (q, k, v)
+        del tq, tk, tv
+        torch.cuda.empty_cache()
+
+    w, ft, un = results[args.workload]
+    fl = useful_flops(w)
+    tf = fl / (ft["ms_step"] * 1e-3) / 1e12
+    tf_un = fl / (un["ms_step"] * 1e-3) / 1e12
+    tf_kernel = fl / (ft["ms_main"] * 1e-3) / 1e12
+    out = {
+        "metric": "FT-attention TFLOP/s at 1 GPU, % overhead vs unprotected, % MFMA peak",
+        "value": round(tf, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ft["ms_step"], 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"cfg{w.cfg} {w.name}: batch {w.batch}, heads {w.heads}, seq {w.seq}, head_dim {w.head_dim}, "
+                               f"{'bf16' if w.dtype else 'fp16'} in, fp32 out, {'causal' if w.causal else 'non-causal'}, fault-free",
+                   "block_m": ft["block_m"], "block_n": ft["block_n"], "stride": 8},
+        "unprotected_tflops": round(tf_un, 2), "unprotected_ms_per_step": round(un["ms_step"], 4),
+        "ft_overhead_pct": round((ft["ms_step"] / un["ms_step"] - 1) * 100, 2),
+        "mfma_peak_pct": round(tf / MFMA_PEAK_TFLOPS * 100, 2),
+        "ms_encode": round(ft["ms_encode"], 4), "ms_fused_kernel": round(ft["ms_main"], 4),
+        "ms_fused_kernel_unprotected": round(un["ms_main"], 4),
+        "fast_path_rechecks": ft["rechecks"], "events": ft["events"],
+        "roofline": {"bound": "mfma", "achieved": round(tf_kernel, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(tf_kernel / MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                     "kernel": "ftattn_main (fused FT attention)", "algorithmic_flops_per_launch": fl},
+    }
+    if args.all_workloads:
+        out["other_workloads"] = {
+            f"cfg{c}": {"ft_tflops": round(useful_flops(ww) / f_["ms_step"] / 1e9, 2),
+                        "unprotected_tflops": round(useful_flops(ww) / u_["ms_step"] / 1e9, 2),
+                        "ft_overhead_pct": round((f_["ms_step"] / u_["ms_step"] - 1) * 100, 2)}
+            for c, (ww, f_, u_) in results.items() if c != args.workload}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, *keep)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -128,6 +128,13 @@ int ftattn_forward(ftattn_ctx* ctx, const void* q, const void* k, const void* v,
                    const ftattn_fault* faults, int32_t n_faults, void* hip_stream);
 /* Waits for the last forward of this context and exposes its flags, residuals and events. */
 int ftattn_report(ftattn_ctx* ctx, ftattn_report_view* out);
+/* Kernel timing for benchmarks.  After ftattn_set_timing(ctx, 1) every forward brackets its
+ * encode kernels and its fused kernel with HIP events on the stream it launches on;
+ * ftattn_get_timing waits for the last forward and returns the two durations in milliseconds:
+ * ms[0] = encode (Algorithm 1, "Encode tensor checksum", plus operand conversion / transposition),
+ * ms[1] = fused attention kernel (all other steps of Algorithm 1). */
+int ftattn_set_timing(ftattn_ctx* ctx, int32_t enabled);
+int ftattn_get_timing(ftattn_ctx* ctx, float ms[2]);
 int ftattn_destroy(ftattn_ctx* ctx);
 /* Message of the last failure on this context ("" if none).  ctx may be NULL: returns the
  * message of the last failed ftattn_create of the calling thread. */

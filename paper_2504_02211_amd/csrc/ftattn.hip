@@ -36,6 +36,8 @@ struct ftattn_ctx {
   std::vector<float> resmax;
   hipStream_t last_stream = nullptr;
   bool ran = false;
+  bool timing = false;
+  hipEvent_t ev[3] = {nullptr, nullptr, nullptr};   // before encode, before fused kernel, after
   std::string err;
 };
 
@@ -61,6 +63,7 @@ static void release(ftattn_ctx* c) {
   (void)hipFree(c->d_recheck); (void)hipFree(c->d_resmax);
   if (c->h_faults) (void)hipHostFree(c->h_faults);
   if (c->h_fault_off) (void)hipHostFree(c->h_fault_off);
+  for (hipEvent_t e : c->ev) if (e) (void)hipEventDestroy(e);
   delete c;
 }
 
@@ -226,6 +229,7 @@ extern "C" int ftattn_forward(ftattn_ctx* c, const void* q, const void* k, const
   int n_resmax = c->BH * c->Ti * 4;
   ftattn_reset<<<(n_resmax + 255) / 256, 256, 0, st>>>(c->d_ev_count, c->d_recheck, c->d_resmax, n_resmax);
 
+  if (c->timing) HIP_TRY(c, hipEventRecord(c->ev[0], st));
   // ---- encode (Algorithm 1: "Encode tensor checksum"), once per key tile for all row tiles
   const _Float16* qh = (const _Float16*)q;
   if (e.in_dtype == FTATTN_BF16) {
@@ -257,8 +261,10 @@ extern "C" int ftattn_forward(ftattn_ctx* c, const void* q, const void* k, const
   a.events = c->d_events; a.ev_count = c->d_ev_count; a.max_events = e.max_events;
   a.resmax = c->d_resmax; a.recheck = c->d_recheck;
   main_fn f = select_kernel(D, c->NW, c->NQ, ft, e.causal != 0);
+  if (c->timing) HIP_TRY(c, hipEventRecord(c->ev[1], st));
   hipLaunchKernelGGL(f, dim3(c->BH * c->Ti), dim3(c->NW * 64), lds_bytes(D), st, a);
   HIP_TRY(c, hipGetLastError());
+  if (c->timing) HIP_TRY(c, hipEventRecord(c->ev[2], st));
   c->last_stream = st;
   c->ran = true;
   return FTATTN_OK;
@@ -308,6 +314,26 @@ extern "C" int ftattn_report(ftattn_ctx* c, ftattn_report_view* out) {
   out->rowtile_flags = c->rowtile_flags.data();
   out->residual_max = c->resmax.data();
   out->recheck_entries = (int64_t)recheck;
+  return FTATTN_OK;
+}
+
+extern "C" int ftattn_set_timing(ftattn_ctx* c, int32_t enabled) {
+  if (!c) return FTATTN_EINVAL;
+  HIP_TRY(c, hipSetDevice(c->cfg.device));
+  if (enabled)
+    for (hipEvent_t& e : c->ev)
+      if (!e) HIP_TRY(c, hipEventCreate(&e));
+  c->timing = enabled != 0;
+  return FTATTN_OK;
+}
+
+extern "C" int ftattn_get_timing(ftattn_ctx* c, float ms[2]) {
+  if (!c || !ms) return FTATTN_EINVAL;
+  if (!c->timing || !c->ran) return fail(c, FTATTN_EINVAL, "timing is not enabled or no forward has run");
+  HIP_TRY(c, hipSetDevice(c->cfg.device));
+  HIP_TRY(c, hipEventSynchronize(c->ev[2]));
+  HIP_TRY(c, hipEventElapsedTime(&ms[0], c->ev[0], c->ev[1]));
+  HIP_TRY(c, hipEventElapsedTime(&ms[1], c->ev[1], c->ev[2]));
   return FTATTN_OK;
 }
 

@@ -22,7 +22,7 @@ FT_OFF, FT_CORRECT, FT_DETECT = 0, 1, 2
 OK, EINVAL, EUNSUPPORTED, EHIP, ENOMEM = 0, -1, -2, -3, -4
 
 EXPORTS = ("ftattn_create", "ftattn_get_config", "ftattn_forward", "ftattn_report", "ftattn_destroy",
-           "ftattn_last_error")
+           "ftattn_last_error", "ftattn_set_timing", "ftattn_get_timing")
 
 
 class Config(C.Structure):
@@ -68,6 +68,12 @@ def load_library() -> C.CDLL:
         return _lib
     if not os.path.exists(LIB_PATH):
         raise FileNotFoundError(f"{LIB_PATH} is not built; run `python -m paper_2504_02211_amd.build`")
+    # The caller's tensors live in torch's HIP runtime; load that runtime first so that this
+    # library binds to the same one instead of bringing a second copy into the process.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(LIB_PATH)
     lib.ftattn_create.argtypes = [C.POINTER(Config), C.POINTER(C.c_void_p)]
     lib.ftattn_get_config.argtypes = [C.c_void_p, C.POINTER(Config)]
@@ -75,9 +81,12 @@ def load_library() -> C.CDLL:
                                    C.c_int32, C.c_void_p]
     lib.ftattn_report.argtypes = [C.c_void_p, C.POINTER(ReportView)]
     lib.ftattn_destroy.argtypes = [C.c_void_p]
+    lib.ftattn_set_timing.argtypes = [C.c_void_p, C.c_int32]
+    lib.ftattn_get_timing.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
     lib.ftattn_last_error.argtypes = [C.c_void_p]
     lib.ftattn_last_error.restype = C.c_char_p
-    for n in ("ftattn_create", "ftattn_get_config", "ftattn_forward", "ftattn_report", "ftattn_destroy"):
+    for n in ("ftattn_create", "ftattn_get_config", "ftattn_forward", "ftattn_report", "ftattn_destroy",
+              "ftattn_set_timing", "ftattn_get_timing"):
         getattr(lib, n).restype = C.c_int
     _lib = lib
     return lib
@@ -150,6 +159,19 @@ class FtAttn:
         if rc != OK:
             raise FtAttnError(rc, self.lib.ftattn_last_error(self.handle).decode())
         return Report(view, self.config.batch, self.config.heads)
+
+    def set_timing(self, enabled: bool) -> None:
+        rc = self.lib.ftattn_set_timing(self.handle, int(enabled))
+        if rc != OK:
+            raise FtAttnError(rc, self.lib.ftattn_last_error(self.handle).decode())
+
+    def get_timing(self):
+        """(encode ms, fused-kernel ms) of the last forward; needs set_timing(True)."""
+        ms = (C.c_float * 2)()
+        rc = self.lib.ftattn_get_timing(self.handle, ms)
+        if rc != OK:
+            raise FtAttnError(rc, self.lib.ftattn_last_error(self.handle).decode())
+        return float(ms[0]), float(ms[1])
 
     def close(self) -> None:
         if self.handle:
