@@ -17,7 +17,7 @@ def build(verbose: bool = True, extra_flags=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-Wno-unused-value", "-Wno-unknown-attributes",
+           "-Wno-unused-value", "-Wno-unknown-attributes", "-Wno-inline-asm",
            "-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG, "csrc"),
            *extra_flags, *SOURCES, "-o", LIB]
     if verbose:

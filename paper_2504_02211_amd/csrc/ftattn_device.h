@@ -113,6 +113,15 @@ __device__ __forceinline__ half8 lds_v(const char* buf, int row, int chunk) {
   return *reinterpret_cast<const half8*>(buf + row * (BN * 2) + ((chunk ^ swz_v(row)) << 4));
 }
 
+// 16 bytes per lane from global memory straight into LDS at (wave-uniform base + 16*lane).
+// Issued as an opaque instruction so that the compiler does not serialise it against later LDS
+// reads: completion is awaited explicitly with s_waitcnt vmcnt before the barrier that publishes
+// the tile.
+__device__ __forceinline__ void gload_lds16(const void* g, const char* lds_dst) {
+  uint32_t base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char*)lds_dst;
+  asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(base) : "memory", "m0");
+}
+
 // Asynchronous copy of one encoded key tile and one encoded value tile into LDS.
 template <int D, int NW, bool FT>
 __device__ __forceinline__ void load_tiles(const _Float16* kc_tile, const _Float16* vt_tile, char* bufk, char* bufv,
@@ -128,7 +137,7 @@ __device__ __forceinline__ void load_tiles(const _Float16* kc_tile, const _Float
       int row = L / KCH, c = (L % KCH) ^ swz_k<D>(row);
       const _Float16* g = kc_tile + row * D + c * 8;
       char* dst = bufk + __builtin_amdgcn_readfirstlane(ins) * 1024;
-      __builtin_amdgcn_global_load_lds(g, (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+      gload_lds16(g, dst);
     }
   }
 #pragma unroll
@@ -139,7 +148,7 @@ __device__ __forceinline__ void load_tiles(const _Float16* kc_tile, const _Float
       int row = L / 8, c = (L % 8) ^ swz_v(row);
       const _Float16* g = vt_tile + row * BN + c * 8;
       char* dst = bufv + __builtin_amdgcn_readfirstlane(ins) * 1024;
-      __builtin_amdgcn_global_load_lds(g, (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+      gload_lds16(g, dst);
     }
   }
 }
