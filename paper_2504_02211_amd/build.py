@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "libftattn.so")
 SOURCES = [os.path.join(PKG, "csrc", "ftattn.hip")]
-HEADERS = [os.path.join(PKG, "csrc", "ftattn_device.h"), os.path.join(ROOT, "include", "ftattn.h")]
+HEADERS = [os.path.join(PKG, "csrc", "ftattn_device.h"), os.path.join(PKG, "csrc", "ftattn_main.h"), os.path.join(ROOT, "include", "ftattn.h")]
 
 
 def build(verbose: bool = True, extra_flags=()) -> str:

@@ -1,7 +1,7 @@
 // Host side of the fault-tolerant fused attention library: the C ABI of include/ftattn.h.
 // Validation, fault bucketing, launches and the report are here; every arithmetic step of
 // the attention pass runs in the kernels of ftattn_device.h.
-#include "ftattn_device.h"
+#include "ftattn_main.h"
 
 #include <algorithm>
 #include <cmath>
@@ -15,7 +15,7 @@ using namespace ftattn;
 
 struct ftattn_ctx {
   ftattn_config cfg;          // effective configuration
-  int BH, Ti, Tj, BM, NW, NQ;
+  int BH, Ti, Tj, BM;
   // device scratch
   _Float16* qh = nullptr;     // fp16 copy of Q (bf16 input only)
   _Float16* kc = nullptr;
@@ -69,24 +69,22 @@ static void release(ftattn_ctx* c) {
 
 typedef void (*main_fn)(const KArgs);
 
-template <int D, int NW, int NQ>
+template <int D>
 static main_fn pick(bool ft, bool causal) {
-  if (ft) return causal ? ftattn_main<D, NW, NQ, true, true> : ftattn_main<D, NW, NQ, true, false>;
-  return causal ? ftattn_main<D, NW, NQ, false, true> : ftattn_main<D, NW, NQ, false, false>;
+  if (ft) return causal ? ftattn_main<D, true, true> : ftattn_main<D, true, false>;
+  return causal ? ftattn_main<D, false, true> : ftattn_main<D, false, false>;
 }
 
-static main_fn select_kernel(int D, int NW, int NQ, bool ft, bool causal) {
-  if (D == 128) {
-    if (NW == 4 && NQ == 2) return pick<128, 4, 2>(ft, causal);
-    if (NW == 4 && NQ == 1) return pick<128, 4, 1>(ft, causal);
-  } else if (D == 64) {
-    if (NW == 4 && NQ == 2) return pick<64, 4, 2>(ft, causal);
-    if (NW == 4 && NQ == 1) return pick<64, 4, 1>(ft, causal);
-  }
+static main_fn select_kernel(int D, bool ft, bool causal) {
+  if (D == 128) return pick<128>(ft, causal);
+  if (D == 64) return pick<64>(ft, causal);
   return nullptr;
 }
 
-static size_t lds_bytes(int D) { return 2 * (size_t)((BN + CKR) * D * 2 + (D + CKR) * BN * 2); }
+static size_t lds_bytes(int D, bool ft) {
+  if (D == 128) return NSTAGE * (size_t)(ft ? Unit<128, true>::BYTES : Unit<128, false>::BYTES);
+  return NSTAGE * (size_t)(ft ? Unit<64, true>::BYTES : Unit<64, false>::BYTES);
+}
 
 extern "C" int ftattn_create(const ftattn_config* cfg, ftattn_ctx** out) {
   if (!cfg || !out) return fail(nullptr, FTATTN_EINVAL, "null argument");
@@ -100,7 +98,7 @@ extern "C" int ftattn_create(const ftattn_config* cfg, ftattn_ctx** out) {
   if (cfg->ft_mode < 0 || cfg->ft_mode > 2) return fail(nullptr, FTATTN_EINVAL, "ft_mode out of range");
   if (cfg->stride != 0 && cfg->stride != 8) return fail(nullptr, FTATTN_EUNSUPPORTED, "stride must be 8");
   if (cfg->block_n != 0 && cfg->block_n != BN) return fail(nullptr, FTATTN_EUNSUPPORTED, "block_n must be 64");
-  if (cfg->block_m != 0 && cfg->block_m != 128 && cfg->block_m != 256) return fail(nullptr, FTATTN_EUNSUPPORTED, "block_m must be 128 or 256");
+  if (cfg->block_m != 0 && cfg->block_m != BM) return fail(nullptr, FTATTN_EUNSUPPORTED, "block_m must be 256");
   if (cfg->causal != 0 && cfg->causal != 1) return fail(nullptr, FTATTN_EINVAL, "causal must be 0 or 1");
 
   ftattn_ctx* c = new (std::nothrow) ftattn_ctx();
@@ -116,12 +114,8 @@ extern "C" int ftattn_create(const ftattn_config* cfg, ftattn_ctx** out) {
   if (e.max_events <= 0) e.max_events = 65536;
   c->BH = e.batch * e.heads;
   c->Tj = (e.seq + BN - 1) / BN;
-  if (e.block_m == 0) {
-    e.block_m = 128;
-  }
-  c->BM = e.block_m;
-  c->NW = 4;
-  c->NQ = c->BM / 128;
+  e.block_m = BM;
+  c->BM = BM;
   c->Ti = (e.seq + c->BM - 1) / c->BM;
 
   hipError_t he = hipSetDevice(e.device);
@@ -161,9 +155,9 @@ extern "C" int ftattn_create(const ftattn_config* cfg, ftattn_ctx** out) {
   CREATE_TRY(hipMemset(c->d_resmax, 0, sizeof(uint32_t) * (size_t)c->BH * c->Ti * 4));
   for (int ft = 0; ft < 2; ++ft)
     for (int ca = 0; ca < 2; ++ca) {
-      main_fn f = select_kernel(D, c->NW, c->NQ, ft != 0, ca != 0);
+      main_fn f = select_kernel(D, ft != 0, ca != 0);
       if (!f) { release(c); return fail(nullptr, FTATTN_EUNSUPPORTED, "no kernel for this tile shape"); }
-      CREATE_TRY(hipFuncSetAttribute((const void*)f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes(D)));
+      CREATE_TRY(hipFuncSetAttribute((const void*)f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes(D, ft != 0)));
     }
   CREATE_TRY(hipDeviceSynchronize());
 #undef CREATE_TRY
@@ -260,9 +254,9 @@ extern "C" int ftattn_forward(ftattn_ctx* c, const void* q, const void* k, const
   a.fault_off = n_faults > 0 ? c->d_fault_off : nullptr;
   a.events = c->d_events; a.ev_count = c->d_ev_count; a.max_events = e.max_events;
   a.resmax = c->d_resmax; a.recheck = c->d_recheck;
-  main_fn f = select_kernel(D, c->NW, c->NQ, ft, e.causal != 0);
+  main_fn f = select_kernel(D, ft, e.causal != 0);
   if (c->timing) HIP_TRY(c, hipEventRecord(c->ev[1], st));
-  hipLaunchKernelGGL(f, dim3(c->BH * c->Ti), dim3(c->NW * 64), lds_bytes(D), st, a);
+  hipLaunchKernelGGL(f, dim3(c->BH * c->Ti), dim3(NWAVE * 64), lds_bytes(D, ft), st, a);
   HIP_TRY(c, hipGetLastError());
   if (c->timing) HIP_TRY(c, hipEventRecord(c->ev[2], st));
   c->last_stream = st;

@@ -1,0 +1,623 @@
+// The fused fault-tolerant attention kernel (gfx950 / CDNA4): Algorithm 1 of the paper from
+// GEMM I to the final store, for one (batch, head, 256-query row tile) per workgroup.
+//
+// Execution shape.  Eight waves of 64 lanes; wave w owns queries 32w .. 32w+31 of the row tile.
+// The waves form two groups of four (one wave of each group per SIMD) that run half an iteration
+// apart: while one group is in its MATRIX phase (GEMM II of key tile i and GEMM I of key tile
+// i+1, back to back on the MFMA pipe) the other is in its SOFTMAX phase (max, exp, product-form
+// check, row-sum, rescale: vector ALU only), and at every workgroup barrier they trade places.
+// Key / value tiles arrive in LDS by direct global-to-LDS loads into a ring of three stages;
+// stage u holds V_u^T and K_{u+1}, the two operands one matrix phase reads.
+//
+// Register layout: see ftattn_device.h (scores transposed, one query per lane, the four
+// stride-8 checksum classes of a lane and all their folds in the lane's own registers).
+#pragma once
+#include "ftattn_device.h"
+
+namespace ftattn {
+
+constexpr int NWAVE = 8;
+constexpr int BM = NWAVE * 32;
+constexpr int NSTAGE = 3;
+
+template <int D, bool FT> struct Unit {
+  static constexpr int KROWS = FT ? BN + CKR : BN;
+  static constexpr int VROWS = FT ? D + CKR : D;
+  static constexpr int KBYTES = KROWS * D * 2;
+  static constexpr int VBYTES = VROWS * BN * 2;
+  static constexpr int BYTES = KBYTES + VBYTES;
+  static constexpr int K_INSTR = KBYTES / 1024;     // one instruction moves 64 lanes x 16 bytes
+  static constexpr int V_INSTR = VBYTES / 1024;
+  static constexpr int KPW = (K_INSTR + NWAVE - 1) / NWAVE;
+  static constexpr int VPW = (V_INSTR + NWAVE - 1) / NWAVE;
+  // instructions issued per unit by a wave of group 0 (waves 0..3) and of group 1 (waves 4..7)
+  static constexpr int N0 = KPW + VPW;
+  static constexpr int N1 = K_INSTR / NWAVE + V_INSTR / NWAVE;
+  static_assert(K_INSTR % NWAVE == 0 || K_INSTR % NWAVE == 4, "load split must be uniform per group");
+  static_assert(V_INSTR % NWAVE == 0 || V_INSTR % NWAVE == 4, "load split must be uniform per group");
+};
+
+// 16 bytes per lane from (uniform base + per-lane byte offset) straight into LDS at
+// (uniform LDS address + 16*lane).  Opaque to the compiler on purpose (see gload_lds16 above).
+__device__ __forceinline__ void gload_lds16_off(const void* base, uint32_t byte_off, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_addr) : "memory", "m0");
+}
+
+template <int N> __device__ __forceinline__ void wait_vmcnt() { __builtin_amdgcn_s_waitcnt(0x0F70 | N); }
+
+__device__ __forceinline__ void phase_barrier() {
+  __builtin_amdgcn_sched_barrier(0);
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_sched_barrier(0);
+}
+
+template <int D, bool FT, bool CAUSAL>
+__global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
+  using U = Unit<D, FT>;
+  constexpr int NSLAB = D / 16;     // k-slabs of GEMM I
+  constexpr int NFB = D / 32;       // 32-feature blocks of O^T
+  constexpr int NFOLD_V = D / 8;
+  constexpr int KCH = D / 8;        // 16-byte chunks per key row
+  constexpr int KT_ELEMS = (BN + CKR) * D, VT_ELEMS = (D + CKR) * BN;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+  // ---- workgroup -> (head, row tile).  Workgroup ids go round-robin over the 8 XCDs; give each
+  // XCD a contiguous range of work so that workgroups sharing K/V of a head share an L2.
+  const int total = gridDim.x;
+  int logical;
+  {
+    int id = blockIdx.x, xcd = id & 7, slot = id >> 3, qn = total >> 3, rn = total & 7;
+    logical = xcd * qn + (xcd < rn ? xcd : rn) + slot;
+  }
+  const int bh = logical / a.Ti;
+  const int ti = CAUSAL ? a.Ti - 1 - (logical % a.Ti) : (logical % a.Ti);   // heavy row tiles first
+  const int tid = threadIdx.x, lane = tid & 63, lq = lane & 31, hi = lane >> 5;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int grp = wave >> 2;
+  const int N = a.N;
+  const int row0_cta = ti * BM;
+  const int row0_w = row0_cta + wave * 32;
+  const int last_row_cta = (row0_cta + BM < N ? row0_cta + BM : N) - 1;
+  const int nj = CAUSAL ? (last_row_cta / BN + 1) : a.Tj;         // key tiles of the workgroup
+  int nj_w = 0;                                                   // key tiles this wave takes part in
+  if (row0_w < N) {
+    int last_row_w = (row0_w + 32 < N ? row0_w + 32 : N) - 1;
+    nj_w = CAUSAL ? (last_row_w / BN + 1) : a.Tj;
+  }
+  const int row = row0_w + lq;
+  const float sl2 = a.scale_log2;
+
+  const _Float16* kc_head = a.kc + (size_t)bh * a.Tj * KT_ELEMS;
+  const _Float16* vt_head = a.vt + (size_t)bh * a.Tj * VT_ELEMS;
+  const uint32_t smem_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
+
+  // ---- per-lane source offsets of this wave's load instructions (the same for every tile)
+  uint32_t koff[U::KPW], voff[U::VPW];
+#pragma unroll
+  for (int i = 0; i < U::KPW; ++i) {
+    int L = (wave + NWAVE * i) * 64 + lane;
+    int r = L / KCH, c = (L % KCH) ^ swz_k<D>(r);
+    koff[i] = (uint32_t)(r * D + c * 8) * 2u;
+  }
+#pragma unroll
+  for (int i = 0; i < U::VPW; ++i) {
+    int L = (wave + NWAVE * i) * 64 + lane;
+    int r = L / 8, c = (L % 8) ^ swz_v(r);
+    voff[i] = (uint32_t)(r * BN + c * 8) * 2u;
+  }
+  // unit u = { V_u^T, K_{u+1} } goes to stage (u+1) mod 3; tiles that do not exist are replaced by
+  // a neighbour (never read) so that every unit costs the same number of instructions
+  auto issue_unit = [&](int u) __attribute__((always_inline)) {
+    const int st = (u + 1) % NSTAGE;
+    const uint32_t lds = smem_base + (uint32_t)st * U::BYTES;
+    const int jk = u + 1 < a.Tj ? u + 1 : a.Tj - 1, jv = u > 0 ? u : 0;
+    const _Float16* kt = kc_head + (size_t)jk * KT_ELEMS;
+    const _Float16* vtile = vt_head + (size_t)jv * VT_ELEMS;
+#pragma unroll
+    for (int i = 0; i < U::KPW; ++i) {
+      int ins = wave + NWAVE * i;
+      if ((i + 1) * NWAVE <= U::K_INSTR || ins < U::K_INSTR) gload_lds16_off(kt, koff[i], lds + (uint32_t)ins * 1024u);
+    }
+#pragma unroll
+    for (int i = 0; i < U::VPW; ++i) {
+      int ins = wave + NWAVE * i;
+      if ((i + 1) * NWAVE <= U::V_INSTR || ins < U::V_INSTR)
+        gload_lds16_off(vtile, voff[i], lds + (uint32_t)U::KBYTES + (uint32_t)ins * 1024u);
+    }
+  };
+
+  // faults of this workgroup
+  int fcur = 0, fend = 0;
+  const DevFault* __restrict__ F = a.faults;
+  if (a.fault_off != nullptr) { fcur = a.fault_off[bh * a.Ti + ti]; fend = a.fault_off[bh * a.Ti + ti + 1]; }
+
+  issue_unit(-1);
+  issue_unit(0);
+  if (nj >= 2) issue_unit(1);
+
+  // ---- Q_i^T as MFMA B operand: lane (query lq, half hi) holds Q[row][16*slab + 8*hi .. +7]
+  half8 qf[NSLAB];
+  {
+    const _Float16* qp = a.q + ((size_t)bh * N + (row < N ? row : 0)) * D + 8 * hi;
+#pragma unroll
+    for (int sl = 0; sl < NSLAB; ++sl) {
+      half8 v = *reinterpret_cast<const half8*>(qp + 16 * sl);
+      if (row >= N) v = (half8)(_Float16)0;
+      qf[sl] = v;
+    }
+  }
+
+  float16v o[NFB], oc, s[2], sc;
+  half8 ph[2][2];             // P^T in fp16, B operand of GEMM II: [key block][8-key half]
+#pragma unroll
+  for (int fb = 0; fb < NFB; ++fb) o[fb] = (float16v)0.f;
+  oc = (float16v)0.f;
+  float m_run = -__builtin_inff(), l_part = 0.f, l_low = 0.f, dev_max = 0.f;
+  unsigned rechecks = 0;
+
+  // GEMM I of one key tile: S^T = K_j Q^T, checksum block = K^c Q^T  (eq. (15), (16))
+  auto gemm1 = [&](const char* bk) __attribute__((always_inline)) {
+    s[0] = (float16v)0.f; s[1] = (float16v)0.f;
+    if (FT) sc = (float16v)0.f;
+    half8 ka[2][3];
+    ka[0][0] = lds_k<D>(bk, lq, hi);
+    ka[0][1] = lds_k<D>(bk, 32 + lq, hi);
+    if (FT) ka[0][2] = lds_k<D>(bk, 64 + lq, hi);
+#pragma unroll
+    for (int sl = 0; sl < NSLAB; ++sl) {
+      const int cur = sl & 1, nxt = cur ^ 1;
+      if (sl + 1 < NSLAB) {
+        ka[nxt][0] = lds_k<D>(bk, lq, 2 * (sl + 1) + hi);
+        ka[nxt][1] = lds_k<D>(bk, 32 + lq, 2 * (sl + 1) + hi);
+        if (FT) ka[nxt][2] = lds_k<D>(bk, 64 + lq, 2 * (sl + 1) + hi);
+      }
+      s[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ka[cur][0], qf[sl], s[0], 0, 0, 0);
+      s[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ka[cur][1], qf[sl], s[1], 0, 0, 0);
+      if (FT) sc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ka[cur][2], qf[sl], sc, 0, 0, 0);
+    }
+  };
+
+  // GEMM II of one key tile: O^T += V_j^T P^T  (+ checksum block); the rescale was applied before
+  auto gemm2 = [&](const char* bv) __attribute__((always_inline)) {
+    constexpr int NA = FT ? NFB + 1 : NFB;
+    half8 va[2][NFB + 1];
+#pragma unroll
+    for (int x = 0; x < NA; ++x) va[0][x] = lds_v(bv, 32 * x + lq, 2 * hi);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int cur = t & 1, nxt = cur ^ 1, kb = t >> 1, n = t & 1;
+      if (t + 1 < 4) {
+        const int kb1 = (t + 1) >> 1, n1 = (t + 1) & 1;
+#pragma unroll
+        for (int x = 0; x < NA; ++x) va[nxt][x] = lds_v(bv, 32 * x + lq, 4 * kb1 + 2 * hi + n1);
+      }
+#pragma unroll
+      for (int fb = 0; fb < NFB; ++fb) o[fb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[cur][fb], ph[kb][n], o[fb], 0, 0, 0);
+      if (FT) oc = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[cur][NFB], ph[kb][n], oc, 0, 0, 0);
+    }
+  };
+
+  // ---- prologue: the first key tile's scores; group 1 starts one barrier later than group 0
+  if (grp == 0) { if (nj >= 2) wait_vmcnt<2 * U::N0>(); else wait_vmcnt<U::N0>(); }
+  else { if (nj >= 2) wait_vmcnt<2 * U::N1>(); else wait_vmcnt<U::N1>(); }
+  phase_barrier();
+  if (grp == 1) phase_barrier();
+  if (nj_w > 0) gemm1(smem);
+  if (grp == 1) { if (nj >= 2) wait_vmcnt<U::N1>(); else wait_vmcnt<0>(); }
+  phase_barrier();
+
+  for (int i = 0; i < nj; ++i) {
+    const int k0 = i * BN;
+    const bool on = i < nj_w;
+    const char* stage = smem + ((i + 1) % NSTAGE) * U::BYTES;
+    const bool tile_has_fault = fcur < fend && F[fcur].kv_tile == i;
+
+    // =========================================================== softmax phase
+    if (grp == 1 && i + 2 < nj) issue_unit(i + 2);
+    if (on) {
+      const bool g_mask = (CAUSAL && k0 + BN - 1 > row0_w) || (k0 + BN > N);
+
+      // ---- injection point: raw scores
+      if (tile_has_fault) {
+        for (int fi = fcur; fi < fend && F[fi].kv_tile == i; ++fi) {
+          if (F[fi].stage != FTATTN_ST_S) continue;
+          int lr = F[fi].row - row0_w, kl = F[fi].col - k0, bit = F[fi].bit;
+          bool mine = lr >= 0 && lr < 32 && lane == lr + 32 * ((kl & 7) >> 2);
+          int tkb = kl >> 5, tv = 4 * ((kl & 31) >> 3) + (kl & 3);
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s[kb][v] = flip_if(s[kb][v], mine && tkb == kb && tv == v, bit);
+        }
+      }
+
+      float p[2][16];
+      float mx, m_new, negm;
+      bool recheck = g_mask;
+
+      if (!g_mask) {
+        // ============ reduce max, exp (fast path: no masked entry in this tile)
+        float m0 = fmax2(s[0][0], s[0][1]), m1 = fmax2(s[1][0], s[1][1]);
+#pragma unroll
+        for (int v = 2; v < 16; v += 2) {
+          m0 = fmax2(fmax2(m0, s[0][v]), s[0][v + 1]);
+          m1 = fmax2(fmax2(m1, s[1][v]), s[1][v + 1]);
+        }
+        mx = max32(fmax2(m0, m1));
+        m_new = fmax2(m_run, mx);
+        negm = -m_new * sl2;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) p[kb][v] = ex2(__builtin_fmaf(s[kb][v], sl2, negm));
+      } else {
+        // ============ same with the causal / sequence-end mask applied per element
+        mx = -__builtin_inff();
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            int key = k0 + key_of(kb, v, hi);
+            bool ok = key < N && (!CAUSAL || key <= row);
+            mx = fmax2(mx, ok ? s[kb][v] : -__builtin_inff());
+          }
+        mx = max32(mx);
+        m_new = fmax2(m_run, mx);
+        negm = -m_new * sl2;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            int key = k0 + key_of(kb, v, hi);
+            bool ok = key < N && (!CAUSAL || key <= row);
+            p[kb][v] = ok ? ex2(__builtin_fmaf(s[kb][v], sl2, negm)) : 0.f;
+          }
+      }
+
+      // ---- injection point: exponentials
+      if (tile_has_fault) {
+        for (int fi = fcur; fi < fend && F[fi].kv_tile == i; ++fi) {
+          if (F[fi].stage != FTATTN_ST_EXP) continue;
+          int lr = F[fi].row - row0_w, kl = F[fi].col - k0, bit = F[fi].bit;
+          bool mine = lr >= 0 && lr < 32 && lane == lr + 32 * ((kl & 7) >> 2);
+          int tkb = kl >> 5, tv = 4 * ((kl & 31) >> 3) + (kl & 3);
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) p[kb][v] = flip_if(p[kb][v], mine && tkb == kb && tv == v, bit);
+        }
+      }
+
+      if (FT) {
+        if (!g_mask) {
+          // ============ unified product-form check of GEMM I, subtraction and exp
+          // (Algorithm 1, first "if"; Section 3.4 case 2).  For class c the product of its 8
+          // exponentials must equal exp2(sl2*check1 - 8*m).  Both sides are divided by that
+          // prediction, two factors at a time, so the running product stays near one.
+          bool bad = false;
+          float dv[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            float chk = sc[r] + sc[4 + r];
+            float e = __builtin_fmaf(chk, sl2, (float)NFOLD_K * negm);
+            float s2 = ex2(e * (-2.0f / NFOLD_K));
+            float pr = ((p[0][r] * p[0][4 + r]) * s2) * ((p[0][8 + r] * p[0][12 + r]) * s2);
+            pr *= ((p[1][r] * p[1][4 + r]) * s2) * ((p[1][8 + r] * p[1][12 + r]) * s2);
+            dv[r] = __builtin_fabsf(pr - 1.0f);
+            bad |= !(dv[r] <= a.tau_fast);
+          }
+          recheck = wave_any(bad);
+          if (recheck) ++rechecks;
+          else dev_max = fmax2(fmax2(fmax2(dev_max, dv[0]), fmax2(dv[1], dv[2])), dv[3]);   // largest deviation that passed
+        }
+        if (recheck) {
+          // ============ exact re-evaluation (rare: a fast check tripped, or the tile is masked).
+          // lambda = ln prod P - (sigma*check1_eff - n_valid*m) = sum_l (ln P_l - x_l) - sigma*R1.
+          bool lin_fixed = false, logged = false;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            float chk1 = sc[r] + sc[4 + r];
+            float sum1 = 0.f, E = 0.f;
+            int nvalid = 0;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+              for (int gg = 0; gg < 4; ++gg) {
+                int v = 4 * gg + r, key = k0 + key_of(kb, v, hi);
+                bool ok = key < N && (!CAUSAL || key <= row);
+                float sv = s[kb][v];
+                sum1 += sv;
+                float t = __builtin_fmaf(sv, sl2, negm);
+                float pe = ex2(t);
+                if (ok) {
+                  ++nvalid;
+                  if (as_u(pe) != as_u(p[kb][v])) E += lg2(p[kb][v]) - t;
+                }
+              }
+            float R1 = chk1 - sum1;
+            float lam = LN2 * E - a.scale * R1;
+            bool det = nvalid > 0 && !(__builtin_fabsf(lam) <= a.eps1);
+            if (det) {
+              logged = true;
+              bool linear = !(a.scale * __builtin_fabsf(R1) <= 0.5f * a.eps1);
+              if (linear) {
+                float chk2 = sc[8 + r] + sc[12 + r];
+                float sum2 = 0.f, big = -1.f;
+                int l_big = -1;
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                  for (int gg = 0; gg < 4; ++gg) {
+                    float sv = s[kb][4 * gg + r];
+                    sum2 += (float)(4 * kb + gg + 1) * sv;
+                    float mag = finitef(sv) ? __builtin_fabsf(sv) : __builtin_inff();
+                    if (mag > big) { big = mag; l_big = 4 * kb + gg; } else if (mag == big) { l_big = -1; }
+                  }
+                float ratio = (chk2 - sum2) / R1;
+                int lstar = -1;
+                if (finitef(ratio)) {
+                  float c = __builtin_rintf(ratio) - 1.0f;
+                  if (c >= 0.f && c < (float)NFOLD_K) lstar = (int)c;
+                } else {
+                  lstar = l_big;   // residuals left the fp32 range: the fold of overwhelming size
+                }
+                int col = lstar >= 0 ? k0 + 32 * (lstar >> 2) + 8 * (lstar & 3) + 4 * hi + r : -1;
+                bool fix = a.correct && lstar >= 0;
+                log_event(a, bh, FTATTN_CHECK_S, i, row, col, lam, fix ? 1 : 0);
+                if (fix) {
+                  float rest = 0.f;
+#pragma unroll
+                  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int gg = 0; gg < 4; ++gg)
+                      if (4 * kb + gg != lstar) rest += s[kb][4 * gg + r];
+                  float val = chk1 - rest;
+#pragma unroll
+                  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int gg = 0; gg < 4; ++gg)
+                      if (4 * kb + gg == lstar) s[kb][4 * gg + r] = val;
+                  lin_fixed = true;
+                }
+              } else {
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                  for (int gg = 0; gg < 4; ++gg) {
+                    int v = 4 * gg + r, key = k0 + key_of(kb, v, hi);
+                    bool ok = key < N && (!CAUSAL || key <= row);
+                    float pe = ex2(__builtin_fmaf(s[kb][v], sl2, negm));
+                    if (ok && as_u(pe) != as_u(p[kb][v])) {
+                      log_event(a, bh, FTATTN_CHECK_EXP, i, row, key, lam, a.correct ? 1 : 0);
+                      if (a.correct) p[kb][v] = pe;
+                    }
+                  }
+              }
+            }
+          }
+          // the event log's stores complete out of order with loads: drain before the counted waits
+          if (wave_any(logged)) wait_vmcnt<0>();
+          // a repaired score changes the row's maximum and exponentials: recompute the row
+          // (the exchange is a wave-wide operation: evaluate it outside any per-lane short circuit)
+          const float partner_fixed = xchg32(lin_fixed ? 1.f : 0.f, hi);
+          bool redo = lin_fixed | (partner_fixed != 0.f);
+          if (wave_any(redo)) {
+            float mx2 = -__builtin_inff();
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+              for (int v = 0; v < 16; ++v) {
+                int key = k0 + key_of(kb, v, hi);
+                bool ok = key < N && (!CAUSAL || key <= row);
+                mx2 = fmax2(mx2, ok ? s[kb][v] : -__builtin_inff());
+              }
+            mx2 = max32(mx2);
+            if (redo) {
+              mx = mx2;
+              m_new = fmax2(m_run, mx);
+              negm = -m_new * sl2;
+            }
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+              for (int v = 0; v < 16; ++v) {
+                int key = k0 + key_of(kb, v, hi);
+                bool ok = key < N && (!CAUSAL || key <= row);
+                float pe = ok ? ex2(__builtin_fmaf(s[kb][v], sl2, negm)) : 0.f;
+                if (redo) p[kb][v] = pe;
+              }
+          }
+        }
+      }
+
+      // ============ reduce sum (row-sum and its lower bound carried with the same rescale)
+      const float al = ex2(__builtin_fmaf(m_run, sl2, negm));
+      float ps0 = p[0][0] + p[0][1], ps1 = p[1][0] + p[1][1];
+#pragma unroll
+      for (int v = 2; v < 16; v += 2) { ps0 += p[0][v] + p[0][v + 1]; ps1 += p[1][v] + p[1][v + 1]; }
+      l_part = l_part * al + (ps0 + ps1);
+      if (FT) l_low = l_low * al + ex2(__builtin_fmaf(mx, sl2, negm));
+      m_run = m_new;
+
+      // ---- injection point: row-sum
+      if (tile_has_fault) {
+        for (int fi = fcur; fi < fend && F[fi].kv_tile == i; ++fi) {
+          if (F[fi].stage != FTATTN_ST_ROWSUM) continue;
+          int lr = F[fi].row - row0_w;
+          bool mine = lr >= 0 && lr < 32 && lq == lr;
+          float full = sum32(l_part);
+          float flipped = flip_if(full, true, F[fi].bit);
+          if (mine) l_part = hi ? 0.f : flipped;
+        }
+      }
+
+      // P -> fp16 in B-operand order: registers 8n..8n+7 of a key block feed MFMA n
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int n = 0; n < 2; ++n)
+#pragma unroll
+          for (int x = 0; x < 8; ++x) ph[kb][n][x] = (_Float16)p[kb][8 * n + x];
+
+      // ============ rescale of the running output (Algorithm 1: diag(e^{m_old - m_new}) O)
+      if (wave_any(al != 1.f)) {
+#pragma unroll
+        for (int fb = 0; fb < NFB; ++fb) o[fb] *= al;
+        if (FT) oc *= al;
+      }
+    }
+    if (grp == 0) { if (i + 1 < nj) wait_vmcnt<U::N0>(); else wait_vmcnt<0>(); }
+    phase_barrier();
+
+    // =========================================================== matrix phase
+    if (grp == 0 && i + 2 < nj) issue_unit(i + 2);
+    __builtin_amdgcn_s_setprio(1);
+    if (on) gemm2(stage + U::KBYTES);
+    if (i + 1 < nj_w) gemm1(stage);
+    __builtin_amdgcn_s_setprio(0);
+
+    // ---- injection point: output accumulator
+    if (tile_has_fault) {
+      if (on) {
+        for (int fi = fcur; fi < fend && F[fi].kv_tile == i; ++fi) {
+          if (F[fi].stage != FTATTN_ST_OACC) continue;
+          int lr = F[fi].row - row0_w, col = F[fi].col, bit = F[fi].bit;
+          bool mine = lr >= 0 && lr < 32 && lane == lr + 32 * ((col & 7) >> 2);
+          int tfb = col >> 5, tv = 4 * ((col & 31) >> 3) + (col & 3);
+#pragma unroll
+          for (int fb = 0; fb < NFB; ++fb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[fb][v] = flip_if(o[fb][v], mine && tfb == fb && tv == v, bit);
+        }
+      }
+      while (fcur < fend && F[fcur].kv_tile == i) ++fcur;
+    }
+    if (grp == 1) { if (i + 2 < nj) wait_vmcnt<U::N1>(); else wait_vmcnt<0>(); }
+    phase_barrier();
+  }
+  if (grp == 0) phase_barrier();
+
+  // ================= after the loop: row-sum range check, normalisation, sum-form check, store
+  float rmax_o = 0.f, rmax_u = 0.f, rmax_l = 0.f;
+  {
+    const bool real = row < N;
+    float l = sum32(l_part);
+    if (FT) {
+      float Ub = CAUSAL ? (float)(row + 1 < N ? row + 1 : N) : (float)N;
+      float lo = l_low;
+      bool detl = real && !(lo * (1.f - a.delta_l) <= l && l <= Ub * (1.f + a.delta_l));
+      if (!detl && real) { rmax_u = fmax2(rmax_u, l / Ub); rmax_l = fmax2(rmax_l, lo / l); }
+      if (detl) {
+        if (hi == 0) log_event(a, bh, FTATTN_CHECK_L, -1, row, 0, l, a.correct ? 1 : 0);
+        if (a.correct) l = lo;     // the approximation of Section 3.4, "optimized EFTA"
+      }
+    }
+    float inv = 1.0f / l;
+#pragma unroll
+    for (int fb = 0; fb < NFB; ++fb) o[fb] *= inv;
+    if (FT) {
+      oc *= inv;
+      bool bad = false;
+      float R[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        float sum1 = 0.f;
+#pragma unroll
+        for (int fb = 0; fb < NFB; ++fb)
+#pragma unroll
+          for (int gg = 0; gg < 4; ++gg) sum1 += o[fb][4 * gg + r];
+        R[r] = (oc[r] + oc[4 + r]) - sum1;
+        bool d = real && !(__builtin_fabsf(R[r]) <= a.tau_o);
+        bad |= d;
+        if (!d && real) rmax_o = fmax2(rmax_o, __builtin_fabsf(R[r]));
+      }
+      if (wave_any(bad)) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          if (real && !(__builtin_fabsf(R[r]) <= a.tau_o)) {
+            float chk1 = oc[r] + oc[4 + r], chk2 = oc[8 + r] + oc[12 + r];
+            float sum2 = 0.f, big = -1.f;
+            int l_big = -1;
+#pragma unroll
+            for (int fb = 0; fb < NFB; ++fb)
+#pragma unroll
+              for (int gg = 0; gg < 4; ++gg) {
+                float ov = o[fb][4 * gg + r];
+                sum2 += (float)(4 * fb + gg + 1) * ov;
+                float mag = finitef(ov) ? __builtin_fabsf(ov) : __builtin_inff();
+                if (mag > big) { big = mag; l_big = 4 * fb + gg; } else if (mag == big) { l_big = -1; }
+              }
+            float ratio = (chk2 - sum2) / R[r];
+            int lstar = -1;
+            if (finitef(ratio)) {
+              float c = __builtin_rintf(ratio) - 1.0f;
+              if (c >= 0.f && c < (float)NFOLD_V) lstar = (int)c;
+            } else {
+              lstar = l_big;
+            }
+            int col = lstar >= 0 ? 8 * lstar + 4 * hi + r : -1;
+            bool fix = a.correct && lstar >= 0;
+            log_event(a, bh, FTATTN_CHECK_O, -1, row, col, R[r], fix ? 1 : 0);
+            if (fix) {
+              float rest = 0.f;
+#pragma unroll
+              for (int fb = 0; fb < NFB; ++fb)
+#pragma unroll
+                for (int gg = 0; gg < 4; ++gg)
+                  if (4 * fb + gg != lstar) rest += o[fb][4 * gg + r];
+              float val = chk1 - rest;
+#pragma unroll
+              for (int fb = 0; fb < NFB; ++fb)
+#pragma unroll
+                for (int gg = 0; gg < 4; ++gg)
+                  if (4 * fb + gg == lstar) o[fb][4 * gg + r] = val;
+            }
+          }
+        }
+      }
+    }
+    // ---- store: lane holds features 32*fb + 8*gg + 4*hi + (0..3) of its query
+    if (real) {
+      size_t base = ((size_t)bh * N + row) * D;
+#pragma unroll
+      for (int fb = 0; fb < NFB; ++fb)
+#pragma unroll
+        for (int gg = 0; gg < 4; ++gg) {
+          int f = 32 * fb + 8 * gg + 4 * hi;
+          float x0 = o[fb][4 * gg], x1 = o[fb][4 * gg + 1], x2 = o[fb][4 * gg + 2], x3 = o[fb][4 * gg + 3];
+          if (a.out_dtype == FTATTN_F32) {
+            float4 v = make_float4(x0, x1, x2, x3);
+            *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.o) + base + f) = v;
+          } else if (a.out_dtype == FTATTN_F16) {
+            _Float16 hv[4] = {(_Float16)x0, (_Float16)x1, (_Float16)x2, (_Float16)x3};
+            *reinterpret_cast<uint2*>(reinterpret_cast<_Float16*>(a.o) + base + f) = *reinterpret_cast<uint2*>(hv);
+          } else {
+            uint32_t u[4] = {as_u(x0), as_u(x1), as_u(x2), as_u(x3)};
+            uint16_t bv16[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+              uint32_t rnd = ((u[x] >> 16) & 1u) + 0x7FFFu;
+              bv16[x] = (u[x] & 0x7F800000u) == 0x7F800000u ? (uint16_t)(u[x] >> 16) : (uint16_t)((u[x] + rnd) >> 16);
+            }
+            *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.o) + base + f) = *reinterpret_cast<uint2*>(bv16);
+          }
+        }
+    }
+  }
+
+  if (FT) {
+    // largest statistics that passed, per row tile (non-negative floats order like their bits)
+    uint32_t* rm = a.resmax + ((size_t)bh * a.Ti + ti) * 4;
+    float vals[4] = {dev_max, rmax_o, rmax_u, rmax_l};
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+      float v = vals[x];
+#pragma unroll
+      for (int off = 32; off >= 1; off >>= 1) v = fmax2(v, __shfl_xor(v, off));
+      if (lane == 0) atomicMax(rm + x, as_u(v));
+    }
+    if (lane == 0 && rechecks) atomicAdd(a.recheck, (unsigned long long)rechecks);
+  }
+}
+
+}  // namespace ftattn
