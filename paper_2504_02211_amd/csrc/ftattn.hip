@@ -69,15 +69,17 @@ static void release(ftattn_ctx* c) {
 
 typedef void (*main_fn)(const KArgs);
 
-template <int D>
+template <int D, bool INJ>
 static main_fn pick(bool ft, bool causal) {
-  if (ft) return causal ? ftattn_main<D, true, true> : ftattn_main<D, true, false>;
-  return causal ? ftattn_main<D, false, true> : ftattn_main<D, false, false>;
+  if (ft) return causal ? ftattn_main<D, true, true, INJ> : ftattn_main<D, true, false, INJ>;
+  return causal ? ftattn_main<D, false, true, INJ> : ftattn_main<D, false, false, INJ>;
 }
 
-static main_fn select_kernel(int D, bool ft, bool causal) {
-  if (D == 128) return pick<128>(ft, causal);
-  if (D == 64) return pick<64>(ft, causal);
+// inject: the variant that carries the fault-injection code; calls without a fault list run the
+// variant that has none of it
+static main_fn select_kernel(int D, bool ft, bool causal, bool inject) {
+  if (D == 128) return inject ? pick<128, true>(ft, causal) : pick<128, false>(ft, causal);
+  if (D == 64) return inject ? pick<64, true>(ft, causal) : pick<64, false>(ft, causal);
   return nullptr;
 }
 
@@ -153,9 +155,9 @@ extern "C" int ftattn_create(const ftattn_config* cfg, ftattn_ctx** out) {
   CREATE_TRY(hipMemset(c->d_ev_count, 0, sizeof(int32_t)));
   CREATE_TRY(hipMemset(c->d_recheck, 0, sizeof(unsigned long long)));
   CREATE_TRY(hipMemset(c->d_resmax, 0, sizeof(uint32_t) * (size_t)c->BH * c->Ti * 4));
-  for (int ft = 0; ft < 2; ++ft)
-    for (int ca = 0; ca < 2; ++ca) {
-      main_fn f = select_kernel(D, ft != 0, ca != 0);
+  for (int v = 0; v < 8; ++v) {
+      const int ft = v & 1, ca = (v >> 1) & 1;
+      main_fn f = select_kernel(D, ft != 0, ca != 0, (v >> 2) != 0);
       if (!f) { release(c); return fail(nullptr, FTATTN_EUNSUPPORTED, "no kernel for this tile shape"); }
       CREATE_TRY(hipFuncSetAttribute((const void*)f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes(D, ft != 0)));
     }
@@ -254,7 +256,7 @@ extern "C" int ftattn_forward(ftattn_ctx* c, const void* q, const void* k, const
   a.fault_off = n_faults > 0 ? c->d_fault_off : nullptr;
   a.events = c->d_events; a.ev_count = c->d_ev_count; a.max_events = e.max_events;
   a.resmax = c->d_resmax; a.recheck = c->d_recheck;
-  main_fn f = select_kernel(D, ft, e.causal != 0);
+  main_fn f = select_kernel(D, ft, e.causal != 0, n_faults > 0);
   if (c->timing) HIP_TRY(c, hipEventRecord(c->ev[1], st));
   hipLaunchKernelGGL(f, dim3(c->BH * c->Ti), dim3(NWAVE * 64), lds_bytes(D, ft), st, a);
   HIP_TRY(c, hipGetLastError());

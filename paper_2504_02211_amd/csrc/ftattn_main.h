@@ -43,6 +43,9 @@ __device__ __forceinline__ void gload_lds16_off(const void* base, uint32_t byte_
   asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_addr) : "memory", "m0");
 }
 
+struct yes { static constexpr bool value = true; };
+struct no { static constexpr bool value = false; };
+
 template <int N> __device__ __forceinline__ void wait_vmcnt() { __builtin_amdgcn_s_waitcnt(0x0F70 | N); }
 
 __device__ __forceinline__ void phase_barrier() {
@@ -51,7 +54,7 @@ __device__ __forceinline__ void phase_barrier() {
   __builtin_amdgcn_sched_barrier(0);
 }
 
-template <int D, bool FT, bool CAUSAL>
+template <int D, bool FT, bool CAUSAL, bool INJ>
 __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
   using U = Unit<D, FT>;
   constexpr int NSLAB = D / 16;     // k-slabs of GEMM I
@@ -129,7 +132,7 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
   // faults of this workgroup
   int fcur = 0, fend = 0;
   const DevFault* __restrict__ F = a.faults;
-  if (a.fault_off != nullptr) { fcur = a.fault_off[bh * a.Ti + ti]; fend = a.fault_off[bh * a.Ti + ti + 1]; }
+  if (INJ && a.fault_off != nullptr) { fcur = a.fault_off[bh * a.Ti + ti]; fend = a.fault_off[bh * a.Ti + ti + 1]; }
 
   issue_unit(-1);
   issue_unit(0);
@@ -155,54 +158,63 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
   float m_run = -__builtin_inff(), l_part = 0.f, l_low = 0.f, dev_max = 0.f;
   unsigned rechecks = 0;
 
-  // GEMM I of one key tile: S^T = K_j Q^T, checksum block = K^c Q^T  (eq. (15), (16))
-  auto gemm1 = [&](const char* bk) __attribute__((always_inline)) {
-    s[0] = (float16v)0.f; s[1] = (float16v)0.f;
-    if (FT) sc = (float16v)0.f;
-    half8 ka[2][3];
-    ka[0][0] = lds_k<D>(bk, lq, hi);
-    ka[0][1] = lds_k<D>(bk, 32 + lq, hi);
-    if (FT) ka[0][2] = lds_k<D>(bk, 64 + lq, hi);
-#pragma unroll
-    for (int sl = 0; sl < NSLAB; ++sl) {
-      const int cur = sl & 1, nxt = cur ^ 1;
-      if (sl + 1 < NSLAB) {
-        ka[nxt][0] = lds_k<D>(bk, lq, 2 * (sl + 1) + hi);
-        ka[nxt][1] = lds_k<D>(bk, 32 + lq, 2 * (sl + 1) + hi);
-        if (FT) ka[nxt][2] = lds_k<D>(bk, 64 + lq, 2 * (sl + 1) + hi);
-      }
-      s[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ka[cur][0], qf[sl], s[0], 0, 0, 0);
-      s[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(ka[cur][1], qf[sl], s[1], 0, 0, 0);
-      if (FT) sc = __builtin_amdgcn_mfma_f32_32x32x16_f16(ka[cur][2], qf[sl], sc, 0, 0, 0);
+  // The matrix phase as one stream of (LDS operand read, MFMA) pairs: first GEMM II of a key tile,
+  //   O^T += V_j^T P^T (+ checksum block; the rescale was applied in the softmax phase),
+  // then GEMM I of the next key tile,
+  //   S^T = K_j Q^T, checksum block = K^c Q^T  (eq. (15), (16)).
+  // The wave that runs this phase has the MFMA pipe of its SIMD to itself (its partner wave is in
+  // the softmax phase), so the LDS latency must be hidden inside the stream: operand k+RING-1 is
+  // requested before MFMA k is issued, and the scheduler is told to keep exactly that order.
+  constexpr int NA2 = FT ? NFB + 1 : NFB;      // A operands per k-step of GEMM II
+  constexpr int NA1 = FT ? 3 : 2;              // A operands per k-slab of GEMM I
+  constexpr int RING = 6;
+  auto matrix_stream = [&](const char* bv, const char* bk, auto do2_tag, auto do1_tag) __attribute__((always_inline)) {
+    constexpr bool DO2 = decltype(do2_tag)::value, DO1 = decltype(do1_tag)::value;
+    constexpr int N2 = DO2 ? 4 * NA2 : 0, N1 = DO1 ? NSLAB * NA1 : 0, NOPS = N2 + N1;
+    if (DO1) {
+      s[0] = (float16v)0.f; s[1] = (float16v)0.f;
+      if (FT) sc = (float16v)0.f;
     }
-  };
-
-  // GEMM II of one key tile: O^T += V_j^T P^T  (+ checksum block); the rescale was applied before
-  auto gemm2 = [&](const char* bv) __attribute__((always_inline)) {
-    constexpr int NA = FT ? NFB + 1 : NFB;
-    half8 va[2][NFB + 1];
-#pragma unroll
-    for (int x = 0; x < NA; ++x) va[0][x] = lds_v(bv, 32 * x + lq, 2 * hi);
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const int cur = t & 1, nxt = cur ^ 1, kb = t >> 1, n = t & 1;
-      if (t + 1 < 4) {
-        const int kb1 = (t + 1) >> 1, n1 = (t + 1) & 1;
-#pragma unroll
-        for (int x = 0; x < NA; ++x) va[nxt][x] = lds_v(bv, 32 * x + lq, 4 * kb1 + 2 * hi + n1);
+    half8 buf[RING];
+    auto load_op = [&](int k) __attribute__((always_inline)) -> half8 {
+      if (k < N2) {
+        const int t = k / NA2, x = k % NA2;
+        return lds_v(bv, 32 * x + lq, 4 * (t >> 1) + 2 * hi + (t & 1));
       }
+      const int kk = k - N2, sl = kk / NA1, y = kk % NA1;
+      return lds_k<D>(bk, 32 * y + lq, 2 * sl + hi);
+    };
 #pragma unroll
-      for (int fb = 0; fb < NFB; ++fb) o[fb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[cur][fb], ph[kb][n], o[fb], 0, 0, 0);
-      if (FT) oc = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[cur][NFB], ph[kb][n], oc, 0, 0, 0);
+    for (int k = 0; k < RING - 1 && k < NOPS; ++k) buf[k] = load_op(k);
+#pragma unroll
+    for (int k = 0; k < NOPS; ++k) {
+      if (k + RING - 1 < NOPS) buf[(k + RING - 1) % RING] = load_op(k + RING - 1);
+      const half8 av = buf[k % RING];
+      if (k < N2) {
+        const int t = k / NA2, x = k % NA2;
+        if (x < NFB) o[x] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, ph[t >> 1][t & 1], o[x], 0, 0, 0);
+        else oc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, ph[t >> 1][t & 1], oc, 0, 0, 0);
+      } else {
+        const int kk = k - N2, sl = kk / NA1, y = kk % NA1;
+        if (y < 2) s[y] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, qf[sl], s[y], 0, 0, 0);
+        else sc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, qf[sl], sc, 0, 0, 0);
+      }
     }
+    // pin the order: RING-1 reads, then (MFMA, read) pairs, then the remaining MFMAs
+    __builtin_amdgcn_sched_group_barrier(0x100, RING - 1, 0);
+#pragma unroll
+    for (int k = 0; k + RING - 1 < NOPS; ++k) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+      __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, RING - 1, 0);
   };
-
   // ---- prologue: the first key tile's scores; group 1 starts one barrier later than group 0
   if (grp == 0) { if (nj >= 2) wait_vmcnt<2 * U::N0>(); else wait_vmcnt<U::N0>(); }
   else { if (nj >= 2) wait_vmcnt<2 * U::N1>(); else wait_vmcnt<U::N1>(); }
   phase_barrier();
   if (grp == 1) phase_barrier();
-  if (nj_w > 0) gemm1(smem);
+  if (nj_w > 0) matrix_stream(smem, smem, no{}, yes{});
   if (grp == 1) { if (nj >= 2) wait_vmcnt<U::N1>(); else wait_vmcnt<0>(); }
   phase_barrier();
 
@@ -210,7 +222,7 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
     const int k0 = i * BN;
     const bool on = i < nj_w;
     const char* stage = smem + ((i + 1) % NSTAGE) * U::BYTES;
-    const bool tile_has_fault = fcur < fend && F[fcur].kv_tile == i;
+    const bool tile_has_fault = INJ && fcur < fend && F[fcur].kv_tile == i;
 
     // =========================================================== softmax phase
     if (grp == 1 && i + 2 < nj) issue_unit(i + 2);
@@ -472,8 +484,8 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
     // =========================================================== matrix phase
     if (grp == 0 && i + 2 < nj) issue_unit(i + 2);
     __builtin_amdgcn_s_setprio(1);
-    if (on) gemm2(stage + U::KBYTES);
-    if (i + 1 < nj_w) gemm1(stage);
+    // (after a wave's last key tile GEMM I runs on a tile it does not need: same code, result unused)
+    if (on) matrix_stream(stage + U::KBYTES, stage, yes{}, yes{});
     __builtin_amdgcn_s_setprio(0);
 
     // ---- injection point: output accumulator
