@@ -84,8 +84,8 @@ static main_fn select_kernel(int D, bool ft, bool causal, bool inject) {
 }
 
 static size_t lds_bytes(int D, bool ft) {
-  if (D == 128) return NSTAGE * (size_t)(ft ? Unit<128, true>::BYTES : Unit<128, false>::BYTES);
-  return NSTAGE * (size_t)(ft ? Unit<64, true>::BYTES : Unit<64, false>::BYTES);
+  if (D == 128) return ft ? Unit<128, true>::LDS_TOTAL : Unit<128, false>::LDS_TOTAL;
+  return ft ? Unit<64, true>::LDS_TOTAL : Unit<64, false>::LDS_TOTAL;
 }
 
 extern "C" int ftattn_create(const ftattn_config* cfg, ftattn_ctx** out) {

@@ -30,17 +30,22 @@ template <int D, bool FT> struct Unit {
   static constexpr int V_INSTR = VBYTES / 1024;
   static constexpr int KPW = (K_INSTR + NWAVE - 1) / NWAVE;
   static constexpr int VPW = (V_INSTR + NWAVE - 1) / NWAVE;
-  // instructions issued per unit by a wave of group 0 (waves 0..3) and of group 1 (waves 4..7)
-  static constexpr int N0 = KPW + VPW;
-  static constexpr int N1 = K_INSTR / NWAVE + V_INSTR / NWAVE;
-  static_assert(K_INSTR % NWAVE == 0 || K_INSTR % NWAVE == 4, "load split must be uniform per group");
-  static_assert(V_INSTR % NWAVE == 0 || V_INSTR % NWAVE == 4, "load split must be uniform per group");
+  // Every wave issues NLOAD instructions per unit; a wave that has no real piece left (uneven
+  // split, or no further unit to fetch) aims the instruction at a 1 KB dump area behind the ring,
+  // so that the counted waits below hold for every wave in every iteration.
+  static constexpr int NLOAD = KPW + VPW;
+  static constexpr int DUMP = 1024;
+  static constexpr int LDS_TOTAL = 3 * BYTES + DUMP;
+  static_assert(K_INSTR >= NWAVE && V_INSTR >= NWAVE, "every wave owns at least one piece of each tile");
+  static_assert(2 * NLOAD <= 15, "counted waits use a 4-bit immediate");
 };
 
 // 16 bytes per lane from (uniform base + per-lane byte offset) straight into LDS at
-// (uniform LDS address + 16*lane).  Opaque to the compiler on purpose (see gload_lds16 above).
+// (uniform LDS address + 16*lane).  Opaque to the compiler on purpose (see gload_lds16 above); no
+// memory clobber, so that operand reads of other ring stages may be scheduled around it.  Ordering
+// against barriers and counted waits is kept because all of them are side-effecting instructions.
 __device__ __forceinline__ void gload_lds16_off(const void* base, uint32_t byte_off, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_addr) : "memory", "m0");
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(byte_off), "s"(base), "s"(lds_addr) : "m0");
 }
 
 struct yes { static constexpr bool value = true; };
@@ -98,35 +103,50 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
   uint32_t koff[U::KPW], voff[U::VPW];
 #pragma unroll
   for (int i = 0; i < U::KPW; ++i) {
-    int L = (wave + NWAVE * i) * 64 + lane;
+    int ins = wave + NWAVE * i;
+    if (ins >= U::K_INSTR) ins = wave;             // a piece this wave does not have: any valid source will do
+    int L = ins * 64 + lane;
     int r = L / KCH, c = (L % KCH) ^ swz_k<D>(r);
     koff[i] = (uint32_t)(r * D + c * 8) * 2u;
   }
 #pragma unroll
   for (int i = 0; i < U::VPW; ++i) {
-    int L = (wave + NWAVE * i) * 64 + lane;
+    int ins = wave + NWAVE * i;
+    if (ins >= U::V_INSTR) ins = wave;
+    int L = ins * 64 + lane;
     int r = L / 8, c = (L % 8) ^ swz_v(r);
     voff[i] = (uint32_t)(r * BN + c * 8) * 2u;
   }
-  // unit u = { V_u^T, K_{u+1} } goes to stage (u+1) mod 3; tiles that do not exist are replaced by
-  // a neighbour (never read) so that every unit costs the same number of instructions
-  auto issue_unit = [&](int u) __attribute__((always_inline)) {
+  // unit u = { V_u^T, K_{u+1} } goes to stage (u+1) mod 3.  A unit is fetched in NLOAD pieces per
+  // wave; the pieces of one unit are spread over a matrix phase (see matrix_stream).
+  uint32_t ld_lds = 0;
+  const _Float16* ld_kt = kc_head;
+  const _Float16* ld_vt = vt_head;
+  bool ld_real = false;
+  const uint32_t dump = smem_base + (uint32_t)NSTAGE * U::BYTES;
+  auto prepare_unit = [&](int u, bool real) __attribute__((always_inline)) {
     const int st = (u + 1) % NSTAGE;
-    const uint32_t lds = smem_base + (uint32_t)st * U::BYTES;
-    const int jk = u + 1 < a.Tj ? u + 1 : a.Tj - 1, jv = u > 0 ? u : 0;
-    const _Float16* kt = kc_head + (size_t)jk * KT_ELEMS;
-    const _Float16* vtile = vt_head + (size_t)jv * VT_ELEMS;
-#pragma unroll
-    for (int i = 0; i < U::KPW; ++i) {
-      int ins = wave + NWAVE * i;
-      if ((i + 1) * NWAVE <= U::K_INSTR || ins < U::K_INSTR) gload_lds16_off(kt, koff[i], lds + (uint32_t)ins * 1024u);
+    ld_lds = smem_base + (uint32_t)st * U::BYTES;
+    const int jk = u + 1 < a.Tj ? u + 1 : a.Tj - 1, jv = u > 0 ? (u < a.Tj ? u : a.Tj - 1) : 0;
+    ld_kt = kc_head + (size_t)jk * KT_ELEMS;
+    ld_vt = vt_head + (size_t)jv * VT_ELEMS;
+    ld_real = real;
+  };
+  auto issue_piece = [&](int n) __attribute__((always_inline)) {
+    if (n < U::KPW) {
+      const int ins = wave + NWAVE * n;
+      const bool ok = ld_real && ((n + 1) * NWAVE <= U::K_INSTR || ins < U::K_INSTR);
+      gload_lds16_off(ld_kt, koff[n], ok ? ld_lds + (uint32_t)ins * 1024u : dump);
+    } else {
+      const int m = n - U::KPW, ins = wave + NWAVE * m;
+      const bool ok = ld_real && ((m + 1) * NWAVE <= U::V_INSTR || ins < U::V_INSTR);
+      gload_lds16_off(ld_vt, voff[m], ok ? ld_lds + (uint32_t)U::KBYTES + (uint32_t)ins * 1024u : dump);
     }
+  };
+  auto issue_unit = [&](int u, bool real) __attribute__((always_inline)) {
+    prepare_unit(u, real);
 #pragma unroll
-    for (int i = 0; i < U::VPW; ++i) {
-      int ins = wave + NWAVE * i;
-      if ((i + 1) * NWAVE <= U::V_INSTR || ins < U::V_INSTR)
-        gload_lds16_off(vtile, voff[i], lds + (uint32_t)U::KBYTES + (uint32_t)ins * 1024u);
-    }
+    for (int n = 0; n < U::NLOAD; ++n) issue_piece(n);
   };
 
   // faults of this workgroup
@@ -134,9 +154,9 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
   const DevFault* __restrict__ F = a.faults;
   if (INJ && a.fault_off != nullptr) { fcur = a.fault_off[bh * a.Ti + ti]; fend = a.fault_off[bh * a.Ti + ti + 1]; }
 
-  issue_unit(-1);
-  issue_unit(0);
-  if (nj >= 2) issue_unit(1);
+  issue_unit(-1, true);
+  issue_unit(0, true);
+  issue_unit(1, nj >= 2);
 
   // ---- Q_i^T as MFMA B operand: lane (query lq, half hi) holds Q[row][16*slab + 8*hi .. +7]
   half8 qf[NSLAB];
@@ -168,8 +188,8 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
   constexpr int NA2 = FT ? NFB + 1 : NFB;      // A operands per k-step of GEMM II
   constexpr int NA1 = FT ? 3 : 2;              // A operands per k-slab of GEMM I
   constexpr int RING = 6;
-  auto matrix_stream = [&](const char* bv, const char* bk, auto do2_tag, auto do1_tag) __attribute__((always_inline)) {
-    constexpr bool DO2 = decltype(do2_tag)::value, DO1 = decltype(do1_tag)::value;
+  auto matrix_stream = [&](const char* bv, const char* bk, auto do2_tag, auto do1_tag, auto ld_tag) __attribute__((always_inline)) {
+    constexpr bool DO2 = decltype(do2_tag)::value, DO1 = decltype(do1_tag)::value, LD = decltype(ld_tag)::value;
     constexpr int N2 = DO2 ? 4 * NA2 : 0, N1 = DO1 ? NSLAB * NA1 : 0, NOPS = N2 + N1;
     if (DO1) {
       s[0] = (float16v)0.f; s[1] = (float16v)0.f;
@@ -189,6 +209,8 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
 #pragma unroll
     for (int k = 0; k < NOPS; ++k) {
       if (k + RING - 1 < NOPS) buf[(k + RING - 1) % RING] = load_op(k + RING - 1);
+      // one piece of the next-but-one unit every few MFMAs, so that the memory pipeline never backs up
+      if (LD && k % (NOPS / U::NLOAD) == 1 && k / (NOPS / U::NLOAD) < U::NLOAD) issue_piece(k / (NOPS / U::NLOAD));
       const half8 av = buf[k % RING];
       if (k < N2) {
         const int t = k / NA2, x = k % NA2;
@@ -210,12 +232,11 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
     __builtin_amdgcn_sched_group_barrier(0x008, RING - 1, 0);
   };
   // ---- prologue: the first key tile's scores; group 1 starts one barrier later than group 0
-  if (grp == 0) { if (nj >= 2) wait_vmcnt<2 * U::N0>(); else wait_vmcnt<U::N0>(); }
-  else { if (nj >= 2) wait_vmcnt<2 * U::N1>(); else wait_vmcnt<U::N1>(); }
+  wait_vmcnt<2 * U::NLOAD>();                     // unit -1 has landed
   phase_barrier();
   if (grp == 1) phase_barrier();
-  if (nj_w > 0) matrix_stream(smem, smem, no{}, yes{});
-  if (grp == 1) { if (nj >= 2) wait_vmcnt<U::N1>(); else wait_vmcnt<0>(); }
+  if (nj_w > 0) matrix_stream(smem, smem, no{}, yes{}, no{});
+  if (grp == 1) wait_vmcnt<U::NLOAD>();           // unit 0
   phase_barrier();
 
   for (int i = 0; i < nj; ++i) {
@@ -225,7 +246,6 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
     const bool tile_has_fault = INJ && fcur < fend && F[fcur].kv_tile == i;
 
     // =========================================================== softmax phase
-    if (grp == 1 && i + 2 < nj) issue_unit(i + 2);
     if (on) {
       const bool g_mask = (CAUSAL && k0 + BN - 1 > row0_w) || (k0 + BN > N);
 
@@ -478,14 +498,18 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
         if (FT) oc *= al;
       }
     }
-    if (grp == 0) { if (i + 1 < nj) wait_vmcnt<U::N0>(); else wait_vmcnt<0>(); }
+    if (grp == 0) wait_vmcnt<U::NLOAD>();         // unit i (unit i+1 may still be in flight)
     phase_barrier();
 
     // =========================================================== matrix phase
-    if (grp == 0 && i + 2 < nj) issue_unit(i + 2);
+    prepare_unit(i + 2, i + 2 < nj);
     __builtin_amdgcn_s_setprio(1);
     // (after a wave's last key tile GEMM I runs on a tile it does not need: same code, result unused)
-    if (on) matrix_stream(stage + U::KBYTES, stage, yes{}, yes{});
+    if (on) matrix_stream(stage + U::KBYTES, stage, yes{}, yes{}, yes{});
+    else {
+#pragma unroll
+      for (int n = 0; n < U::NLOAD; ++n) issue_piece(n);
+    }
     __builtin_amdgcn_s_setprio(0);
 
     // ---- injection point: output accumulator
@@ -504,7 +528,7 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
       }
       while (fcur < fend && F[fcur].kv_tile == i) ++fcur;
     }
-    if (grp == 1) { if (i + 2 < nj) wait_vmcnt<U::N1>(); else wait_vmcnt<0>(); }
+    if (grp == 1) wait_vmcnt<U::NLOAD>();         // unit i+1 (unit i+2 may still be in flight)
     phase_barrier();
   }
   if (grp == 0) phase_barrier();
