@@ -17,7 +17,6 @@ struct ftattn_ctx {
   ftattn_config cfg;          // effective configuration
   int BH, Ti, Tj, BM;
   // device scratch
-  _Float16* qh = nullptr;     // fp16 copy of Q (bf16 input only)
   _Float16* kc = nullptr;
   _Float16* vt = nullptr;
   DevFault* d_faults = nullptr;
@@ -58,7 +57,7 @@ static int fail(ftattn_ctx* c, int code, const std::string& msg) {
 
 static void release(ftattn_ctx* c) {
   if (!c) return;
-  (void)hipFree(c->qh); (void)hipFree(c->kc); (void)hipFree(c->vt); (void)hipFree(c->d_faults);
+  (void)hipFree(c->kc); (void)hipFree(c->vt); (void)hipFree(c->d_faults);
   (void)hipFree(c->d_fault_off); (void)hipFree(c->d_events); (void)hipFree(c->d_ev_count);
   (void)hipFree(c->d_recheck); (void)hipFree(c->d_resmax);
   if (c->h_faults) (void)hipHostFree(c->h_faults);
@@ -126,7 +125,6 @@ extern "C" int ftattn_create(const ftattn_config* cfg, ftattn_ctx** out) {
   const int D = e.head_dim;
   size_t n_kc = (size_t)c->BH * c->Tj * (BN + CKR) * D;
   size_t n_vt = (size_t)c->BH * c->Tj * (D + CKR) * BN;
-  size_t n_q = (size_t)c->BH * e.seq * D;
   c->fault_cap = 1 << 16;
 #define CREATE_TRY(expr)                                                                                  \
   do {                                                                                                    \
@@ -138,7 +136,6 @@ extern "C" int ftattn_create(const ftattn_config* cfg, ftattn_ctx** out) {
       return rc_;                                                                                         \
     }                                                                                                     \
   } while (0)
-  if (e.in_dtype == FTATTN_BF16) CREATE_TRY(hipMalloc((void**)&c->qh, n_q * 2));
   CREATE_TRY(hipMalloc((void**)&c->kc, n_kc * 2));
   CREATE_TRY(hipMalloc((void**)&c->vt, n_vt * 2));
   CREATE_TRY(hipMalloc((void**)&c->d_faults, sizeof(DevFault) * c->fault_cap));
@@ -227,24 +224,19 @@ extern "C" int ftattn_forward(ftattn_ctx* c, const void* q, const void* k, const
 
   if (c->timing) HIP_TRY(c, hipEventRecord(c->ev[0], st));
   // ---- encode (Algorithm 1: "Encode tensor checksum"), once per key tile for all row tiles
-  const _Float16* qh = (const _Float16*)q;
-  if (e.in_dtype == FTATTN_BF16) {
-    size_t n = (size_t)c->BH * N * D;
-    ftattn_convert_q<<<(unsigned)((n / 8 + 255) / 256 + 1), 256, 0, st>>>((const uint16_t*)q, c->qh, n);
-    qh = c->qh;
-  }
   dim3 eg(c->Tj, c->BH);
+  const int bf = e.in_dtype == FTATTN_BF16 ? 1 : 0;
   if (D == 128) {
-    ftattn_encode_k<128><<<eg, 256, 0, st>>>(k, e.in_dtype, c->kc, N, c->Tj, ft ? 1 : 0);
-    ftattn_encode_v<128><<<eg, 256, 0, st>>>(v, e.in_dtype, c->vt, N, c->Tj, ft ? 1 : 0);
+    ftattn_encode_k<128><<<eg, 128, 0, st>>>(k, bf, c->kc, N, c->Tj, ft ? 1 : 0);
+    ftattn_encode_v<128><<<eg, 256, 0, st>>>(v, bf, c->vt, N, c->Tj, ft ? 1 : 0);
   } else {
-    ftattn_encode_k<64><<<eg, 256, 0, st>>>(k, e.in_dtype, c->kc, N, c->Tj, ft ? 1 : 0);
-    ftattn_encode_v<64><<<eg, 256, 0, st>>>(v, e.in_dtype, c->vt, N, c->Tj, ft ? 1 : 0);
+    ftattn_encode_k<64><<<eg, 64, 0, st>>>(k, bf, c->kc, N, c->Tj, ft ? 1 : 0);
+    ftattn_encode_v<64><<<eg, 256, 0, st>>>(v, bf, c->vt, N, c->Tj, ft ? 1 : 0);
   }
 
   // ---- the fused pass
   KArgs a;
-  a.q = qh; a.kc = c->kc; a.vt = c->vt; a.o = o; a.out_dtype = e.out_dtype;
+  a.q = q; a.q_bf16 = bf; a.kc = c->kc; a.vt = c->vt; a.o = o; a.out_dtype = e.out_dtype;
   a.N = N; a.H = e.heads; a.Ti = c->Ti; a.Tj = c->Tj;
   a.scale = e.softmax_scale;
   a.scale_log2 = e.softmax_scale * 1.4426950408889634f;

@@ -42,7 +42,8 @@ constexpr float LN2 = 0.6931471805599453f;
 struct DevFault { int32_t stage, kv_tile, row, col, bit; };
 
 struct KArgs {
-  const _Float16* q;       // [BH][N][D] fp16
+  const void* q;           // [BH][N][D] fp16 or bf16 (q_bf16)
+  int32_t q_bf16;
   const _Float16* kc;      // [BH][Tj][BN + CKR][D]
   const _Float16* vt;      // [BH][Tj][D + CKR][BN]
   void* o;                 // [BH][N][D], fp32 / fp16 / bf16
@@ -133,60 +134,57 @@ __device__ __forceinline__ int key_of(int kb, int v, int hi) { return 32 * kb + 
 
 // ------------------------------------------------------------------ encode kernels
 
-__device__ __forceinline__ float load_as_float(const void* p, size_t idx, int dtype) {
-  if (dtype == FTATTN_F16) return (float)reinterpret_cast<const _Float16*>(p)[idx];
-  return as_f((uint32_t)reinterpret_cast<const uint16_t*>(p)[idx] << 16);
-}
-
-// bf16 -> fp16 copy of Q (fp16 input is used in place)
-__global__ void ftattn_convert_q(const uint16_t* __restrict__ in, _Float16* __restrict__ out, size_t n) {
-  size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 8;
-  if (i + 8 <= n) {
-    uint4v raw = *reinterpret_cast<const uint4v*>(in + i);
-    half8 r;
+// 8 consecutive 16-bit inputs (fp16 or bf16 patterns) -> fp16
+__device__ __forceinline__ half8 to_half8(uint4v raw, bool bf16) {
+  if (!bf16) return __builtin_bit_cast(half8, raw);
+  half8 r;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      r[2 * k] = (_Float16)as_f(raw[k] << 16);
-      r[2 * k + 1] = (_Float16)as_f(raw[k] & 0xFFFF0000u);
-    }
-    *reinterpret_cast<half8*>(out + i) = r;
-  } else {
-    for (; i < n; ++i) out[i] = (_Float16)as_f((uint32_t)in[i] << 16);
+  for (int k = 0; k < 4; ++k) {
+    r[2 * k] = (_Float16)as_f(raw[k] << 16);
+    r[2 * k + 1] = (_Float16)as_f(raw[k] & 0xFFFF0000u);
   }
+  return r;
 }
 
-// One workgroup per (key tile, head): fp16 key rows followed by the four checksum words of
-// check1[c,:] = sum_l K[c+8l,:] and check2[c,:] = sum_l (l+1) K[c+8l,:]   (eq. (13), (14)).
+// One workgroup per (key tile, head), one thread per (checksum class, 16-byte chunk of a row): the
+// thread converts the 8 rows of its class to fp16 and forms, in fp32 registers, the four checksum
+// words of check1[c,:] = sum_l K[c+8l,:] and check2[c,:] = sum_l (l+1) K[c+8l,:]  (eq. (13), (14)).
 template <int D>
-__global__ __launch_bounds__(256) void ftattn_encode_k(const void* __restrict__ k, int dtype, _Float16* __restrict__ kc,
-                                                       int N, int Tj, int with_checksums) {
-  __shared__ float tile[BN][D + 1];
+__global__ __launch_bounds__(D) void ftattn_encode_k(const void* __restrict__ k, int bf16, _Float16* __restrict__ kc,
+                                                     int N, int Tj, int with_checksums) {
+  constexpr int KCH = D / 8;
   const int j = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x;
-  _Float16* out = kc + ((size_t)bh * Tj + j) * ((BN + CKR) * D);
-  for (int e = tid; e < BN * D; e += 256) {
-    int r = e / D, c = e % D, key = j * BN + r;
-    float x = key < N ? load_as_float(k, ((size_t)bh * N + key) * D + c, dtype) : 0.f;
-    _Float16 hx = (_Float16)x;
-    out[r * D + c] = hx;
-    tile[r][c] = (float)hx;
+  const int cls = tid / KCH, ch = tid % KCH;
+  const uint16_t* src = reinterpret_cast<const uint16_t*>(k) + (size_t)bh * N * D + ch * 8;
+  _Float16* out = kc + ((size_t)bh * Tj + j) * ((BN + CKR) * D) + ch * 8;
+  float c1[8], c2[8];
+#pragma unroll
+  for (int x = 0; x < 8; ++x) { c1[x] = 0.f; c2[x] = 0.f; }
+#pragma unroll
+  for (int l = 0; l < NFOLD_K; ++l) {
+    const int r = cls + 8 * l, key = j * BN + r;
+    uint4v raw = (uint4v)0u;
+    if (key < N) raw = *reinterpret_cast<const uint4v*>(src + (size_t)key * D);
+    const half8 h = to_half8(raw, bf16 != 0);
+    *reinterpret_cast<half8*>(out + r * D) = h;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+      const float v = (float)h[x];
+      c1[x] += v;
+      c2[x] += (float)(l + 1) * v;
+    }
   }
   if (!with_checksums) return;
-  __syncthreads();
-  for (int e = tid; e < 8 * D; e += 256) {
-    int cls = e / D, c = e % D;
-    float c1 = 0.f, c2 = 0.f;
+  half8 w0, w1, w2, w3;
 #pragma unroll
-    for (int l = 0; l < NFOLD_K; ++l) {
-      float x = tile[cls + 8 * l][c];
-      c1 += x;
-      c2 += (float)(l + 1) * x;
-    }
-    _Float16 h1 = (_Float16)c1, h2 = (_Float16)c2;
-    out[(BN + cls) * D + c] = h1;
-    out[(BN + 8 + cls) * D + c] = (_Float16)(c1 - (float)h1);
-    out[(BN + 16 + cls) * D + c] = h2;
-    out[(BN + 24 + cls) * D + c] = (_Float16)(c2 - (float)h2);
+  for (int x = 0; x < 8; ++x) {
+    w0[x] = (_Float16)c1[x]; w1[x] = (_Float16)(c1[x] - (float)w0[x]);
+    w2[x] = (_Float16)c2[x]; w3[x] = (_Float16)(c2[x] - (float)w2[x]);
   }
+  *reinterpret_cast<half8*>(out + (BN + cls) * D) = w0;
+  *reinterpret_cast<half8*>(out + (BN + 8 + cls) * D) = w1;
+  *reinterpret_cast<half8*>(out + (BN + 16 + cls) * D) = w2;
+  *reinterpret_cast<half8*>(out + (BN + 24 + cls) * D) = w3;
 }
 
 // position of key kl (0..63) inside the permuted key axis of the V^T tile
@@ -194,42 +192,57 @@ __device__ __forceinline__ int vt_pos(int kl) {
   int kb = kl >> 5, g = (kl >> 3) & 3, hi = (kl >> 2) & 1, r = kl & 3;
   return 32 * kb + 16 * hi + 8 * (g >> 1) + 4 * (g & 1) + r;
 }
+// ... and the key that sits at position p
+__device__ __forceinline__ int vt_key(int p) {
+  int kb = p >> 5, hi = (p >> 4) & 1, G = (p >> 3) & 1, b = (p >> 2) & 1, r = p & 3;
+  return 32 * kb + 16 * G + 8 * b + 4 * hi + r;
+}
 
-// One workgroup per (key tile, head): V^T in fp16 followed by the checksum rows of
+// One workgroup per (key tile, head): V^T in fp16 (16-byte loads, transposition through LDS,
+// 16-byte stores) followed by the checksum rows of
 // check1[key, c] = sum_l V[key, c+8l] and check2 with weights l+1.
 template <int D>
-__global__ __launch_bounds__(256) void ftattn_encode_v(const void* __restrict__ v, int dtype, _Float16* __restrict__ vt,
+__global__ __launch_bounds__(256) void ftattn_encode_v(const void* __restrict__ v, int bf16, _Float16* __restrict__ vt,
                                                        int N, int Tj, int with_checksums) {
-  __shared__ float tile[BN][D + 1];
+  constexpr int KCH = D / 8, PITCH = D + 8;
+  __shared__ __attribute__((aligned(16))) _Float16 tile[BN * PITCH];
+  __shared__ __attribute__((aligned(16))) _Float16 cks[CKR * BN];
   const int j = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x;
+  const uint16_t* src = reinterpret_cast<const uint16_t*>(v) + (size_t)bh * N * D;
   _Float16* out = vt + ((size_t)bh * Tj + j) * ((D + CKR) * BN);
-  for (int e = tid; e < BN * D; e += 256) {
-    int r = e / D, c = e % D, key = j * BN + r;
-    float x = key < N ? load_as_float(v, ((size_t)bh * N + key) * D + c, dtype) : 0.f;
-    tile[r][c] = (float)(_Float16)x;
+  for (int e = tid; e < BN * KCH; e += 256) {
+    const int r = e / KCH, ch = e % KCH, key = j * BN + r;
+    uint4v raw = (uint4v)0u;
+    if (key < N) raw = *reinterpret_cast<const uint4v*>(src + (size_t)key * D + ch * 8);
+    *reinterpret_cast<half8*>(tile + r * PITCH + ch * 8) = to_half8(raw, bf16 != 0);
   }
   __syncthreads();
-  for (int e = tid; e < D * BN; e += 256) {
-    int f = e / BN, kl = e % BN;
-    out[f * BN + vt_pos(kl)] = (_Float16)tile[kl][f];
+  for (int e = tid; e < D * 8; e += 256) {
+    const int f = e >> 3, pc = e & 7;
+    half8 h;
+#pragma unroll
+    for (int x = 0; x < 8; ++x) h[x] = tile[vt_key(8 * pc + x) * PITCH + f];
+    *reinterpret_cast<half8*>(out + f * BN + 8 * pc) = h;
   }
   if (!with_checksums) return;
   for (int e = tid; e < 8 * BN; e += 256) {
-    int cls = e / BN, kl = e % BN;
+    const int cls = e / BN, kl = e % BN;
     float c1 = 0.f, c2 = 0.f;
 #pragma unroll
     for (int l = 0; l < D / 8; ++l) {
-      float x = tile[kl][cls + 8 * l];
+      const float x = (float)tile[kl * PITCH + cls + 8 * l];
       c1 += x;
       c2 += (float)(l + 1) * x;
     }
-    _Float16 h1 = (_Float16)c1, h2 = (_Float16)c2;
-    int p = vt_pos(kl);
-    out[(D + cls) * BN + p] = h1;
-    out[(D + 8 + cls) * BN + p] = (_Float16)(c1 - (float)h1);
-    out[(D + 16 + cls) * BN + p] = h2;
-    out[(D + 24 + cls) * BN + p] = (_Float16)(c2 - (float)h2);
+    const _Float16 h1 = (_Float16)c1, h2 = (_Float16)c2;
+    const int p = vt_pos(kl);
+    cks[cls * BN + p] = h1;
+    cks[(8 + cls) * BN + p] = (_Float16)(c1 - (float)h1);
+    cks[(16 + cls) * BN + p] = h2;
+    cks[(24 + cls) * BN + p] = (_Float16)(c2 - (float)h2);
   }
+  __syncthreads();
+  *reinterpret_cast<half8*>(out + D * BN + tid * 8) = *reinterpret_cast<const half8*>(cks + tid * 8);
 }
 
 // clears the event counter, the recheck counter and the residual maxima (a fill kernel rather

@@ -159,14 +159,15 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
   issue_unit(1, nj >= 2);
 
   // ---- Q_i^T as MFMA B operand: lane (query lq, half hi) holds Q[row][16*slab + 8*hi .. +7]
+  // (bf16 queries are converted here: exact for magnitudes in the fp16 normal range)
   half8 qf[NSLAB];
   {
-    const _Float16* qp = a.q + ((size_t)bh * N + (row < N ? row : 0)) * D + 8 * hi;
+    const uint16_t* qp = reinterpret_cast<const uint16_t*>(a.q) + ((size_t)bh * N + (row < N ? row : 0)) * D + 8 * hi;
 #pragma unroll
     for (int sl = 0; sl < NSLAB; ++sl) {
-      half8 v = *reinterpret_cast<const half8*>(qp + 16 * sl);
-      if (row >= N) v = (half8)(_Float16)0;
-      qf[sl] = v;
+      uint4v raw = *reinterpret_cast<const uint4v*>(qp + 16 * sl);
+      if (row >= N) raw = (uint4v)0u;
+      qf[sl] = to_half8(raw, a.q_bf16 != 0);
     }
   }
 
