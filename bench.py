@@ -96,6 +96,8 @@ def main():
     ap.add_argument("--block-m", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all-workloads", action="store_true", help="also time workloads 2-4 (extra keys)")
+    ap.add_argument("--pmc-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (calibration of HBM byte counters under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -154,6 +156,13 @@ def main():
                         "unprotected_tflops": round(useful_flops(ww) / u_["ms_step"] / 1e9, 2),
                         "ft_overhead_pct": round((f_["ms_step"] / u_["ms_step"] - 1) * 100, 2)}
             for c, (ww, f_, u_) in results.items() if c != args.workload}
+    if args.pmc_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["pmc_copy_bytes_each_way"] = src.numel() * 4
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, *keep)
     print(json.dumps(out))
