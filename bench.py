@@ -28,6 +28,17 @@ def useful_flops(w) -> float:
     return 4.0 * w.head_dim * n * w.batch * w.heads
 
 
+def measured_traffic(cfg: int):
+    """HBM bytes per launch of the FT kernel from the committed rocprofv3 counter summary (None if absent)."""
+    path = os.path.join(ROOT, "profiles", "ftattn_main_cfg5_long_sequence_hbm_traffic.txt")
+    if cfg != 5 or not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch_ft"):
+            return float(line.split("=")[1])
+    return None
+
+
 def time_variant(torch, ftattn, w, tq, tk, tv, ft_mode, steps, warmup, block_m):
     o = torch.empty((w.batch, w.heads, w.seq, w.head_dim), dtype=torch.float32, device="cuda")
     ctx = ftattn.FtAttn(w.batch, w.heads, w.seq, w.head_dim, w.dtype, w.causal, ft_mode=ft_mode, block_m=block_m)
@@ -147,7 +158,7 @@ def main():
         "ms_fused_kernel_unprotected": round(un["ms_main"], 4),
         "fast_path_rechecks": ft["rechecks"], "events": ft["events"],
         "roofline": {"bound": "mfma", "achieved": round(tf_kernel, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(tf_kernel / MFMA_PEAK_TFLOPS, 4), "traffic": None,
+                     "frac": round(tf_kernel / MFMA_PEAK_TFLOPS, 4), "traffic": measured_traffic(w.cfg),
                      "kernel": "ftattn_main (fused FT attention)", "algorithmic_flops_per_launch": fl},
     }
     if args.all_workloads:
