@@ -329,11 +329,12 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
           // prediction, two factors at a time, so the running product stays near one.
           bool bad = false;
           float dv[4];
+          // (2^(-e/4) per pair of factors, e = sl2*check1 + 8*negm the predicted log2 of the product)
+          const float c_chk = sl2 * (-2.0f / NFOLD_K), c_m = -2.0f * negm;
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
             float chk = sc[r] + sc[4 + r];
-            float e = __builtin_fmaf(chk, sl2, (float)NFOLD_K * negm);
-            float s2 = ex2(e * (-2.0f / NFOLD_K));
+            float s2 = ex2(__builtin_fmaf(chk, c_chk, c_m));
             float pr = ((p[0][r] * p[0][4 + r]) * s2) * ((p[0][8 + r] * p[0][12 + r]) * s2);
             pr *= ((p[1][r] * p[1][4 + r]) * s2) * ((p[1][8 + r] * p[1][12 + r]) * s2);
             dv[r] = __builtin_fabsf(pr - 1.0f);
@@ -465,10 +466,22 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
 
       // ============ reduce sum (row-sum and its lower bound carried with the same rescale)
       const float al = ex2(__builtin_fmaf(m_run, sl2, negm));
-      float ps0 = p[0][0] + p[0][1], ps1 = p[1][0] + p[1][1];
+      // P -> fp16 in B-operand order: registers 8n..8n+7 of a key block feed MFMA n.  The row-sum adds
+      // up the converted pairs, the values GEMM II multiplies (dot product with (1, 1), fp32 accumulation).
+      float ps[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
 #pragma unroll
-      for (int v = 2; v < 16; v += 2) { ps0 += p[0][v] + p[0][v + 1]; ps1 += p[1][v] + p[1][v + 1]; }
-      l_part = l_part * al + (ps0 + ps1);
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int n = 0; n < 2; ++n)
+#pragma unroll
+          for (int x = 0; x < 8; x += 2) {
+            half2v pr2;
+            pr2[0] = (_Float16)p[kb][8 * n + x]; pr2[1] = (_Float16)p[kb][8 * n + x + 1];
+            ph[kb][n][x] = pr2[0]; ph[kb][n][x + 1] = pr2[1];
+            const half2v ones = {(_Float16)1.f, (_Float16)1.f};
+            ps[kb][n] = __builtin_amdgcn_fdot2(pr2, ones, ps[kb][n], false);
+          }
+      l_part = l_part * al + ((ps[0][0] + ps[0][1]) + (ps[1][0] + ps[1][1]));
       if (FT) l_low = l_low * al + ex2(__builtin_fmaf(mx, sl2, negm));
       m_run = m_new;
 
@@ -483,14 +496,6 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
           if (mine) l_part = hi ? 0.f : flipped;
         }
       }
-
-      // P -> fp16 in B-operand order: registers 8n..8n+7 of a key block feed MFMA n
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int n = 0; n < 2; ++n)
-#pragma unroll
-          for (int x = 0; x < 8; ++x) ph[kb][n][x] = (_Float16)p[kb][8 * n + x];
 
       // ============ rescale of the running output (Algorithm 1: diag(e^{m_old - m_new}) O)
       if (wave_any(al != 1.f)) {
