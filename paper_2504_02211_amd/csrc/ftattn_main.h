@@ -173,6 +173,9 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
 
   float16v o[NFB], oc, s[2], sc;
   half8 ph[2][2];             // P^T in fp16, B operand of GEMM II: [key block][8-key half]
+  float p[2][16];             // exp(S - m) of the key tile in flight, fp32
+  float ps[2][2];             // its row-sum, one partial per quarter
+  float al = 1.f;             // e^{m_old - m_new} of the key tile in flight
 #pragma unroll
   for (int fb = 0; fb < NFB; ++fb) o[fb] = (float16v)0.f;
   oc = (float16v)0.f;
@@ -189,6 +192,23 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
   constexpr int NA2 = FT ? NFB + 1 : NFB;      // A operands per k-step of GEMM II
   constexpr int NA1 = FT ? 3 : 2;              // A operands per k-slab of GEMM I
   constexpr int RING = 6;
+  // P -> fp16 in B-operand order: registers 8n..8n+7 of key block kb feed the MFMAs of k-step
+  // t = 2*kb + n of GEMM II.  The row-sum adds up the converted pairs, the values GEMM II
+  // multiplies (dot product with (1, 1), fp32 accumulation).  Quarter 0 is converted at the end of
+  // the softmax phase; quarters 1..3 are converted inside the matrix phase, each ahead of its
+  // k-step, where the vector instructions run in the shadow of the wave's own MFMAs.
+  auto convert_quarter = [&](const int t) __attribute__((always_inline)) {
+    const int kb = t >> 1, n = t & 1;
+    ps[kb][n] = 0.f;
+#pragma unroll
+    for (int x = 0; x < 8; x += 2) {
+      half2v pr2;
+      pr2[0] = (_Float16)p[kb][8 * n + x]; pr2[1] = (_Float16)p[kb][8 * n + x + 1];
+      ph[kb][n][x] = pr2[0]; ph[kb][n][x + 1] = pr2[1];
+      const half2v ones = {(_Float16)1.f, (_Float16)1.f};
+      ps[kb][n] = __builtin_amdgcn_fdot2(pr2, ones, ps[kb][n], false);
+    }
+  };
   auto matrix_stream = [&](const char* bv, const char* bk, auto do2_tag, auto do1_tag, auto ld_tag) __attribute__((always_inline)) {
     constexpr bool DO2 = decltype(do2_tag)::value, DO1 = decltype(do1_tag)::value, LD = decltype(ld_tag)::value;
     constexpr int N2 = DO2 ? 4 * NA2 : 0, N1 = DO1 ? NSLAB * NA1 : 0, NOPS = N2 + N1;
@@ -213,6 +233,8 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
       // one piece of the next-but-one unit every few MFMAs, so that the memory pipeline never backs up
       if (LD && k % (NOPS / U::NLOAD) == 1 && k / (NOPS / U::NLOAD) < U::NLOAD) issue_piece(k / (NOPS / U::NLOAD));
       const half8 av = buf[k % RING];
+      if (DO2 && k < 3 * NA2 && k % NA2 == 0) convert_quarter(k / NA2 + 1);     // one k-step ahead of its use
+      if (DO2 && k == 3 * NA2) l_part = l_part * al + ((ps[0][0] + ps[0][1]) + (ps[1][0] + ps[1][1]));   // reduce sum (Algorithm 1)
       if (k < N2) {
         const int t = k / NA2, x = k % NA2;
         if (x < NFB) o[x] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, ph[t >> 1][t & 1], o[x], 0, 0, 0);
@@ -264,7 +286,6 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
         }
       }
 
-      float p[2][16];
       float mx, m_new, negm;
       bool recheck = g_mask;
 
@@ -464,38 +485,12 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
         }
       }
 
-      // ============ reduce sum (row-sum and its lower bound carried with the same rescale)
-      const float al = ex2(__builtin_fmaf(m_run, sl2, negm));
-      // P -> fp16 in B-operand order: registers 8n..8n+7 of a key block feed MFMA n.  The row-sum adds
-      // up the converted pairs, the values GEMM II multiplies (dot product with (1, 1), fp32 accumulation).
-      float ps[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int n = 0; n < 2; ++n)
-#pragma unroll
-          for (int x = 0; x < 8; x += 2) {
-            half2v pr2;
-            pr2[0] = (_Float16)p[kb][8 * n + x]; pr2[1] = (_Float16)p[kb][8 * n + x + 1];
-            ph[kb][n][x] = pr2[0]; ph[kb][n][x + 1] = pr2[1];
-            const half2v ones = {(_Float16)1.f, (_Float16)1.f};
-            ps[kb][n] = __builtin_amdgcn_fdot2(pr2, ones, ps[kb][n], false);
-          }
-      l_part = l_part * al + ((ps[0][0] + ps[0][1]) + (ps[1][0] + ps[1][1]));
+      // ============ rescale factor, lower bound of the row-sum (carried with the same rescale as the
+      // row-sum itself, which is completed in the matrix phase), first quarter of P in fp16
+      al = ex2(__builtin_fmaf(m_run, sl2, negm));
       if (FT) l_low = l_low * al + ex2(__builtin_fmaf(mx, sl2, negm));
       m_run = m_new;
-
-      // ---- injection point: row-sum
-      if (tile_has_fault) {
-        for (int fi = fcur; fi < fend && F[fi].kv_tile == i; ++fi) {
-          if (F[fi].stage != FTATTN_ST_ROWSUM) continue;
-          int lr = F[fi].row - row0_w;
-          bool mine = lr >= 0 && lr < 32 && lq == lr;
-          float full = sum32(l_part);
-          float flipped = flip_if(full, true, F[fi].bit);
-          if (mine) l_part = hi ? 0.f : flipped;
-        }
-      }
+      convert_quarter(0);
 
       // ============ rescale of the running output (Algorithm 1: diag(e^{m_old - m_new}) O)
       if (wave_any(al != 1.f)) {
@@ -518,6 +513,19 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
     }
     __builtin_amdgcn_s_setprio(0);
 
+    // ---- injection point: row-sum (right after the update of this iteration)
+    if (tile_has_fault) {
+      if (on) {
+        for (int fi = fcur; fi < fend && F[fi].kv_tile == i; ++fi) {
+          if (F[fi].stage != FTATTN_ST_ROWSUM) continue;
+          int lr = F[fi].row - row0_w;
+          bool mine = lr >= 0 && lr < 32 && lq == lr;
+          float full = sum32(l_part);
+          float flipped = flip_if(full, true, F[fi].bit);
+          if (mine) l_part = hi ? 0.f : flipped;
+        }
+      }
+    }
     // ---- injection point: output accumulator
     if (tile_has_fault) {
       if (on) {
