@@ -1,0 +1,198 @@
+#!/usr/bin/env python3
+"""Error coverage of the three checks of Algorithm 1 against their thresholds.
+
+The paper's evaluation (Section 4.2, "Error Coverage of Strided ABFT" and "Error Coverage of
+Selective Neuron Value Restriction") reports, for a range of thresholds, how many injected
+computational errors a check detects and how often it fires on error-free data.  This module
+measures the same three curves on the GPU library with its seeded injector:
+
+  product  the per-iteration product-form check (threshold eps1) against flips of S and exp(S - m);
+  sum      the final sum-form check of the output (threshold tau_o) against flips of the output accumulator;
+  range    the range restriction of the row-sum (relative slack delta_l) against flips of the row-sum;
+
+and the error that is left in the output after correction (the approximation of the row-sum by
+its lower bound included).  Every flip hits its own query row, so a detection is attributed to a
+fault by (batch, head, row).  A fault counts as harmful when, left alone, it moves some output of
+its row by more than the parity tolerance of the library (2e-3).
+
+Everything here goes through the C ABI; the inputs are synthetic and seeded.
+
+    python -m paper_2504_02211_amd.coverage --seq 2048 --heads 8 --faults-per-head 48
+"""
+from __future__ import annotations
+
+import argparse
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+from . import ftattn, synth
+
+HARM_TOL = 2e-3
+FAMILIES = ("product", "sum", "range")
+STAGES_OF = {"product": (synth.ST_S, synth.ST_EXP), "sum": (synth.ST_OACC,), "range": (synth.ST_ROWSUM,)}
+CHECKS_OF = {"product": (ftattn.CHECK_S, ftattn.CHECK_EXP), "sum": (ftattn.CHECK_O,), "range": (ftattn.CHECK_L,)}
+DEFAULT_GRIDS = {
+    "product": (1e-4, 1e-3, 3e-3, 1e-2, 3e-2, 1e-1, 3e-1, 1.0, 3.0),
+    "sum": (1e-6, 1e-5, 1e-4, 4e-4, 0.75 * 2.0 ** -9, 5e-3, 2e-2, 1e-1),
+    "range": (1e-7, 1e-6, 1e-5, 1e-4, 2.0 ** -10, 1e-2, 1e-1, 1.0),
+}
+
+
+def draw_faults(batch: int, heads: int, seq: int, head_dim: int, causal: bool, block_n: int, per_head: int,
+                seed: int, bit_lo: int = 0, bit_hi: int = 30) -> np.ndarray:
+    """Seeded single-bit flips, `per_head` per (batch, head), each on a query row of its own."""
+    out: List[Tuple[int, ...]] = []
+    stages = (synth.ST_S, synth.ST_EXP, synth.ST_ROWSUM, synth.ST_OACC)
+    for b in range(batch):
+        for h in range(heads):
+            rows = set()
+            for slot in range(per_head):
+                stream = synth.candidate_stream(seed, b, h, slot, seq, head_dim, block_n, causal,
+                                                (stages[slot % 4],), bit_lo, bit_hi)
+                for _ in range(1000):
+                    f = next(stream)
+                    if f[4] not in rows:
+                        rows.add(f[4])
+                        out.append(f)
+                        break
+    return synth.faults_to_array(out)
+
+
+def _to_torch(bits: np.ndarray, dtype: int):
+    import torch
+    t = torch.from_numpy(bits.view(np.int16)).to("cuda")
+    return t.view(torch.float16 if dtype == synth.F16 else torch.bfloat16)
+
+
+class Runner:
+    """Keeps the operands on the device and runs one forward call per threshold setting."""
+
+    def __init__(self, q: np.ndarray, k: np.ndarray, v: np.ndarray, dtype: int, causal: bool):
+        import torch
+        self.torch = torch
+        self.shape = q.shape
+        self.dtype, self.causal = dtype, causal
+        self.tq, self.tk, self.tv = (_to_torch(x, dtype) for x in (q, k, v))
+
+    def run(self, faults: Optional[np.ndarray], ft_mode: int, **thresholds):
+        torch = self.torch
+        B, H, N, d = self.shape
+        ctx = ftattn.FtAttn(B, H, N, d, self.dtype, self.causal, ft_mode=ft_mode, max_events=1 << 20, **thresholds)
+        o = torch.empty((B, H, N, d), dtype=torch.float32, device="cuda")
+        ctx.forward(self.tq, self.tk, self.tv, o, faults, torch.cuda.current_stream().cuda_stream)
+        rep = ctx.report()
+        out = o.cpu().numpy()
+        cfg = ctx.config
+        ctx.close()
+        return out, rep, cfg
+
+
+def _rows_with_events(rep, checks: Sequence[int]) -> set:
+    e = rep.events
+    m = np.isin(e["check"], checks)
+    return set(zip(e["b"][m].tolist(), e["h"][m].tolist(), e["row"][m].tolist()))
+
+
+def sweep(q: np.ndarray, k: np.ndarray, v: np.ndarray, dtype: int, causal: bool, faults: np.ndarray,
+          grids: Optional[Dict[str, Sequence[float]]] = None) -> Dict[str, object]:
+    """Runs the sweep; returns per-family curves and the post-correction error statistics."""
+    grids = dict(DEFAULT_GRIDS if grids is None else grids)
+    r = Runner(q, k, v, dtype, causal)
+    B, H, N, d = q.shape
+    clean, _, cfg = r.run(None, ftattn.FT_OFF)
+    damaged, _, _ = r.run(faults, ftattn.FT_OFF)
+    with np.errstate(all="ignore"):
+        dmg = np.array([np.nanmax(np.abs(damaged[f[0], f[1], f[4]] - clean[f[0], f[1], f[4]]))
+                        if np.isfinite(damaged[f[0], f[1], f[4]]).all() else np.inf for f in faults])
+    harmful = dmg > HARM_TOL
+    rows_per_check = {"product": None, "sum": B * H * N * 8, "range": B * H * N}
+    bn = cfg.block_n
+    n_tiles = sum((row // bn + 1) if causal else -(-N // bn) for row in range(N))
+    rows_per_check["product"] = B * H * n_tiles * 8
+    key = {"product": "eps1", "sum": "tau_o", "range": "delta_l"}
+    result: Dict[str, object] = {"n_faults": int(len(faults)), "harm_tol": HARM_TOL, "curves": {}}
+    for fam in FAMILIES:
+        sel = np.isin(faults[:, 2], STAGES_OF[fam])
+        curve = []
+        for thr in grids[fam]:
+            _, rep_f, _ = r.run(faults, ftattn.FT_DETECT, **{key[fam]: float(thr)})
+            _, rep_c, _ = r.run(None, ftattn.FT_DETECT, **{key[fam]: float(thr)})
+            hit_rows = _rows_with_events(rep_f, CHECKS_OF[fam])
+            det = np.array([(int(f[0]), int(f[1]), int(f[4])) in hit_rows for f in faults])
+            fa_rows = _rows_with_events(rep_c, CHECKS_OF[fam])
+            n_h, n_b = int((sel & harmful).sum()), int((sel & ~harmful).sum())
+            curve.append({
+                "threshold": float(thr),
+                "harmful": n_h, "harmful_detected": int((sel & harmful & det).sum()),
+                "benign": n_b, "benign_detected": int((sel & ~harmful & det).sum()),
+                # (the other checks run at their defaults and stay silent on clean data; events beyond
+                # the capacity of the log are counted by the library)
+                "false_alarms": int(np.isin(rep_c.events["check"], CHECKS_OF[fam]).sum()) + int(rep_c.n_events_dropped),
+                "false_alarm_rows": len(fa_rows), "checks": rows_per_check[fam],
+            })
+        result["curves"][fam] = curve
+    # what is left after correction at the default thresholds
+    fixed, rep_fix, _ = r.run(faults, ftattn.FT_CORRECT)
+    with np.errstate(all="ignore"):
+        left = np.array([np.nanmax(np.abs(fixed[f[0], f[1], f[4]] - clean[f[0], f[1], f[4]]))
+                         if np.isfinite(fixed[f[0], f[1], f[4]]).all() else np.inf for f in faults])
+    result["after_correction"] = {}
+    for fam in FAMILIES:
+        sel = np.isin(faults[:, 2], STAGES_OF[fam]) & harmful
+        x = left[sel]
+        result["after_correction"][fam] = {
+            "harmful": int(sel.sum()),
+            "within_tol": int((x <= HARM_TOL).sum()),
+            "median": float(np.median(x)) if len(x) else 0.0,
+            "p90": float(np.quantile(x, 0.9)) if len(x) else 0.0,
+            "max": float(x.max()) if len(x) else 0.0,
+        }
+    result["unprotected_damage"] = {"harmful": int(harmful.sum()), "median": float(np.median(dmg[harmful])) if harmful.any() else 0.0}
+    result["per_fault"] = {"damage": dmg, "left": left, "harmful": harmful}
+    return result
+
+
+def to_markdown(res: Dict[str, object]) -> str:
+    names = {"product": "product-form check, threshold eps1 (flips of S and exp)",
+             "sum": "sum-form check of O, threshold tau_o (flips of the output accumulator)",
+             "range": "row-sum range restriction, slack delta_l (flips of the row-sum)"}
+    out = [f"{res['n_faults']} single-bit flips (bits 0-30), harmful = output of the row moves by more than {res['harm_tol']:g}", ""]
+    for fam in FAMILIES:
+        out += [f"**{names[fam]}**", "", "| threshold | harmful detected | benign detected | false alarms on clean data (of checks) |",
+                "|---|---|---|---|"]
+        for c in res["curves"][fam]:
+            hd = f"{c['harmful_detected']}/{c['harmful']}" + (f" ({100.0 * c['harmful_detected'] / c['harmful']:.1f} %)" if c["harmful"] else "")
+            out.append(f"| {c['threshold']:.3g} | {hd} | {c['benign_detected']}/{c['benign']} | {c['false_alarms']} of {c['checks']} |")
+        out.append("")
+    out += ["**left after correction (default thresholds), harmful faults only**", "",
+            "| check | harmful | back within tolerance | median error | 90 % | max |", "|---|---|---|---|---|---|"]
+    for fam in FAMILIES:
+        a = res["after_correction"][fam]
+        out.append(f"| {fam} | {a['harmful']} | {a['within_tol']} | {a['median']:.2e} | {a['p90']:.2e} | {a['max']:.2e} |")
+    return "\n".join(out)
+
+
+def main() -> None:
+    ap = argparse.ArgumentParser(description=__doc__.split("\n")[0])
+    ap.add_argument("--batch", type=int, default=2)
+    ap.add_argument("--heads", type=int, default=8)
+    ap.add_argument("--seq", type=int, default=2048)
+    ap.add_argument("--head-dim", type=int, default=128)
+    ap.add_argument("--dtype", choices=("fp16", "bf16"), default="bf16")
+    ap.add_argument("--non-causal", action="store_true")
+    ap.add_argument("--faults-per-head", type=int, default=48)
+    ap.add_argument("--seed", type=lambda s: int(s, 0), default=0xC0FE)
+    args = ap.parse_args()
+    dtype = synth.F16 if args.dtype == "fp16" else synth.BF16
+    shape = (args.batch, args.heads, args.seq, args.head_dim)
+    q, k, v = synth.gen_qkv(shape, dtype, args.seed)
+    faults = draw_faults(*shape, not args.non_causal, 64, args.faults_per_head, args.seed + 1)
+    res = sweep(q, k, v, dtype, not args.non_causal, faults)
+    print(f"workload: batch {args.batch}, heads {args.heads}, seq {args.seq}, head_dim {args.head_dim}, {args.dtype}, "
+          f"{'non-causal' if args.non_causal else 'causal'}, N(0,1) inputs, seed {args.seed:#x}")
+    print(to_markdown(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,56 @@
+"""GPU: the coverage sweep (detection and false-alarm rates against thresholds) behaves like the
+method says it must, and the library's decisions at non-default thresholds match the oracle's."""
+import numpy as np
+import pytest
+
+from oracle import efta_oracle as orc
+from paper_2504_02211_amd import coverage, ftattn, synth
+import ft_harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def test_sweep_shape_and_oracle_agreement():
+    shape = (1, 2, 640, 64)
+    dtype, causal = synth.F16, True
+    q, k, v = synth.gen_qkv(shape, dtype, 0xC0FE)
+    faults = coverage.draw_faults(*shape, causal, 64, 24, 0xC0FF)
+    assert len(faults) == 48 and len({(f[0], f[1], f[4]) for f in map(tuple, faults)}) == 48
+    grids = {"product": (1e-3, 3e-2, 1.0), "sum": (1e-5, 0.75 * 2.0 ** -9, 2e-2), "range": (1e-6, 2.0 ** -10, 1e-1)}
+    res = coverage.sweep(q, k, v, dtype, causal, faults, grids)
+    print(coverage.to_markdown(res), flush=True)
+    for fam in coverage.FAMILIES:
+        curve = res["curves"][fam]
+        det = [c["harmful_detected"] + c["benign_detected"] for c in curve]
+        fa = [c["false_alarms"] for c in curve]
+        # a looser threshold never detects more and never raises more false alarms
+        assert det == sorted(det, reverse=True), (fam, det)
+        assert fa == sorted(fa, reverse=True), (fam, fa)
+        # the library's default thresholds are silent on clean data
+        assert curve[1]["false_alarms"] == 0, (fam, curve[1])
+    # at the default thresholds every harmful flip of S, exp and the output accumulator is detected,
+    # and the checksum-based corrections bring the output back to within the tolerance
+    for fam in ("product", "sum"):
+        c, a = res["curves"][fam][1], res["after_correction"][fam]
+        assert c["harmful"] > 0 and c["harmful_detected"] == c["harmful"], (fam, c)
+        assert a["within_tol"] == a["harmful"], (fam, a)
+
+    # ---- per-fault decisions at a non-default threshold against the oracle (faults whose statistic
+    # lies within 4x of the threshold are left out: the decision would hinge on rounding)
+    r = coverage.Runner(q, k, v, dtype, causal)
+    for fam, kw in (("product", {"eps1": 0.3}), ("sum", {"tau_o": 2e-2}), ("range", {"delta_l": 1e-1})):
+        _, rep, cfg = r.run(faults, ftattn.FT_DETECT, **kw)
+        prm = H.oracle_params(shape[2], shape[3], causal, block_n=cfg.block_n, scale=cfg.softmax_scale,
+                              eps1=cfg.eps1, tau_o=cfg.tau_o, delta_l=cfg.delta_l, correct=False)
+        got = rep.event_set()
+        compared = 0
+        for f in faults:
+            b, h, row = int(f[0]), int(f[1]), int(f[4])
+            Q, K, V = H.head_f64(q, dtype, b, h), H.head_f64(k, dtype, b, h), H.head_f64(v, dtype, b, h)
+            _, ev, dg = orc.efta_rows(Q[row:row + 1], np.array([row]), K, V, prm, [tuple(int(x) for x in f[2:])])
+            if not orc.fault_is_robust(dg) or len(dg["flipped"]) != 1 or orc.fp32_is_fragile(dg["flipped"][0][1], int(f[2])):
+                continue
+            compared += 1
+            mine = {e for e in got if e[0] == b and e[1] == h and e[4] == row}
+            assert mine == {(b, h) + e for e in ev}, (fam, tuple(f), sorted(mine), ev)
+        assert compared >= 24, compared
