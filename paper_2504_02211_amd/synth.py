@@ -216,3 +216,33 @@ def workload_fault_slots(cfg: int):
 def faults_to_array(faults: List[Tuple[int, ...]]) -> np.ndarray:
     a = np.asarray(faults, dtype=np.int32).reshape(-1, 7)
     return np.ascontiguousarray(a)
+
+
+# ----------------------------------------------------------------------------
+# Linear layer (feed-forward / projection GEMM protected by the same tensor checksums)
+# ----------------------------------------------------------------------------
+# A fault of the linear layer is the integer triple (row, col, bit): bit `bit` of the fp32
+# accumulator of Y[row, col] is inverted after the last accumulation step.
+
+LINEAR_SEED_BASE = 0xF7A7A000
+
+
+def gen_linear(m: int, n: int, k: int, seed: int, x_scale: float = 1.0):
+    """Activations X [m, k] ~ N(0, x_scale^2) and weights W [n, k] ~ N(0, 1/k) (so that the
+    outputs are of order x_scale), rounded to fp16; returns two uint16 arrays.  Rows are drawn
+    from per-row-block Philox streams so that a slice can be regenerated on its own."""
+    x = np.zeros((m, k), np.uint16)
+    w = np.zeros((n, k), np.uint16)
+    for which, arr, rows, sc in ((0, x, m, x_scale), (1, w, n, 1.0 / np.sqrt(k))):
+        for r0 in range(0, rows, 1024):
+            rng = np.random.Generator(np.random.Philox(key=[seed & 0xFFFFFFFFFFFFFFFF, (which << 40) | r0]))
+            nr = min(1024, rows - r0)
+            arr[r0:r0 + nr] = to_bits(rng.standard_normal((nr, k)) * sc, F16)
+    return x, w
+
+
+def linear_fault_stream(seed: int, slot: int, m: int, n: int, bit_lo: int, bit_hi: int) -> Iterator[Tuple[int, int, int]]:
+    """Endless deterministic stream of candidate faults (row, col, bit) for one slot."""
+    rng = np.random.Generator(np.random.Philox(key=[seed & 0xFFFFFFFFFFFFFFFF, (7 << 40) | slot]))
+    while True:
+        yield int(rng.integers(m)), int(rng.integers(n)), int(rng.integers(bit_lo, bit_hi + 1))

@@ -1,0 +1,151 @@
+"""Pins of the strided-ABFT linear-layer oracle against what the paper and the mathematics fix:
+the definition of a matrix product (brute force), the checksum identity of eq. (15), (16) in
+exact integer arithmetic, the location rule and the repair stated after eq. (16) for every
+(class, fold), the stated limit (two errors spaced by a multiple of the stride), and the
+two-word representation of the checksums.  CPU only."""
+import numpy as np
+import pytest
+
+from oracle import ftgemm_oracle as orc
+
+
+def small_ints(rng, shape, lo=-3, hi=4):
+    return rng.integers(lo, hi, size=shape).astype(np.float64)
+
+
+def test_linear_clean_is_the_definition():
+    rng = np.random.default_rng(1)
+    X, W = rng.standard_normal((5, 7)), rng.standard_normal((11, 7))
+    Y = orc.linear_clean(X, W)
+    assert Y.shape == (5, 11)
+    for i in range(5):
+        for j in range(11):
+            assert abs(Y[i, j] - sum(X[i, k] * W[j, k] for k in range(7))) < 1e-12
+
+
+def test_encode_w_against_loops():
+    rng = np.random.default_rng(2)
+    Wb = rng.standard_normal((32, 5))
+    c1, c2 = orc.encode_w(Wb, 8)
+    for c in range(8):
+        for k in range(5):
+            assert abs(c1[c, k] - sum(Wb[c + 8 * l, k] for l in range(4))) < 1e-12
+            assert abs(c2[c, k] - sum((l + 1) * Wb[c + 8 * l, k] for l in range(4))) < 1e-12
+
+
+def test_two_words_hold_the_checksum():
+    rng = np.random.default_rng(3)
+    c = rng.standard_normal((8, 64)) * 37.0
+    hi, lo = orc.two_fp16_words(c)
+    assert np.array_equal(hi, hi.astype(np.float16).astype(np.float64))
+    assert np.array_equal(lo, lo.astype(np.float16).astype(np.float64))
+    assert np.max(np.abs(hi + lo - c) / np.abs(c)) < 2.0 ** -20
+    # a value fp16 holds exactly needs no low word
+    hi, lo = orc.two_fp16_words(np.array([1024.0, -0.5, 3.0]))
+    assert np.array_equal(lo, np.zeros(3))
+
+
+def test_checksum_identity_is_exact_on_integers():
+    """eq. (15): X check1^T equals the stride-8 fold of Y; with small integers every sum is exact,
+    so the residual is exactly zero and nothing is flagged even at a zero threshold."""
+    rng = np.random.default_rng(4)
+    X, W = small_ints(rng, (6, 16)), small_ints(rng, (512, 16))
+    prm = orc.Params(tau_rel=0.0, tau_abs=0.0)
+    Y, ev, dg = orc.ftgemm(X, W, prm)
+    assert ev == []
+    assert np.array_equal(Y, X @ W.T)
+
+
+@pytest.mark.parametrize("block_n", [64, 256])
+def test_location_and_repair_for_every_class_and_fold(block_n):
+    """A single wrong element in (class c, fold l) of block b is named as column
+    n0 + c + 8 l (residual ratio l + 1) and restored exactly."""
+    rng = np.random.default_rng(5)
+    N = 2 * block_n
+    X, W = small_ints(rng, (3, 8)), small_ints(rng, (N, 8))
+    Yref = X @ W.T
+    prm = orc.Params(block_n=block_n, tau_rel=0.0, tau_abs=0.25)
+    for col in range(N):
+        row = col % 3
+        # bit 23 is the lowest exponent bit: the value doubles or halves, or a zero becomes 2^-126
+        f = [(row, col, 23)]
+        damaged = orc.bitflip32(Yref[row, col], 23)
+        if abs(damaged - Yref[row, col]) <= 0.25:
+            continue
+        Y, ev, _ = orc.ftgemm(X, W, prm, f)
+        assert ev == [(row, col, 1)], (col, ev)
+        assert np.array_equal(Y, Yref)
+
+
+def test_detect_only_leaves_the_damage():
+    rng = np.random.default_rng(6)
+    X, W = small_ints(rng, (4, 8), 1, 4), small_ints(rng, (256, 8), 1, 4)
+    Yref = X @ W.T
+    prm = orc.Params(tau_rel=0.0, tau_abs=0.25, correct=False)
+    Y, ev, _ = orc.ftgemm(X, W, prm, [(2, 77, 23)])
+    assert ev == [(2, 77, 0)]
+    assert Y[2, 77] == orc.bitflip32(Yref[2, 77], 23) and Y[2, 77] != Yref[2, 77]
+    Y[2, 77] = Yref[2, 77]
+    assert np.array_equal(Y, Yref)
+
+
+def test_errors_in_different_classes_of_a_row_are_all_repaired():
+    rng = np.random.default_rng(7)
+    X, W = small_ints(rng, (2, 8), 1, 4), small_ints(rng, (256, 8), 1, 4)
+    Yref = X @ W.T
+    prm = orc.Params(tau_rel=0.0, tau_abs=0.25)
+    faults = [(1, 8 * l + c, 23) for c, l in ((0, 3), (1, 31), (5, 0), (7, 17))]
+    Y, ev, _ = orc.ftgemm(X, W, prm, faults)
+    assert sorted(e[1] for e in ev) == sorted(f[1] for f in faults)
+    assert np.array_equal(Y, Yref)
+
+
+def test_two_errors_spaced_by_the_stride_are_seen_but_not_repaired():
+    """The limit stated after eq. (16): errors of one row whose columns differ by a multiple of 8
+    share a checksum class; the class is flagged, the pair cannot be put right."""
+    rng = np.random.default_rng(8)
+    X, W = small_ints(rng, (2, 8), 1, 4), small_ints(rng, (256, 8), 1, 4)
+    Yref = X @ W.T
+    prm = orc.Params(tau_rel=0.0, tau_abs=0.25)
+    Y, ev, _ = orc.ftgemm(X, W, prm, [(0, 3, 23), (0, 3 + 8 * 9, 23)])
+    assert len(ev) == 1 and ev[0][0] == 0
+    assert not np.array_equal(Y, Yref)
+
+
+def test_non_finite_result_is_located_by_magnitude():
+    X = np.array([[1.0, 0.5]])
+    W = np.zeros((256, 2))
+    W[:, 0] = 1.0          # every output is 1.0: exponent field 0x7F, bit 30 turns it into Inf
+    prm = orc.Params()
+    Y, ev, _ = orc.ftgemm(X, W, prm, [(0, 100, 30)])
+    assert ev == [(0, 100, 1)]
+    assert np.array_equal(Y, X @ W.T)
+
+
+def test_ragged_last_block_counts_missing_columns_as_zero():
+    rng = np.random.default_rng(9)
+    N = 256 + 43
+    X, W = small_ints(rng, (3, 8), 1, 4), small_ints(rng, (N, 8), 1, 4)
+    Yref = X @ W.T
+    prm = orc.Params(tau_rel=0.0, tau_abs=0.25)
+    Y, ev, _ = orc.ftgemm(X, W, prm)
+    assert ev == [] and np.array_equal(Y, Yref)
+    Y, ev, _ = orc.ftgemm(X, W, prm, [(1, N - 1, 23)])
+    assert ev == [(1, N - 1, 1)] and np.array_equal(Y, Yref)
+
+
+def test_threshold_is_relative_to_the_summed_magnitude():
+    rng = np.random.default_rng(10)
+    X = rng.standard_normal((8, 64)).astype(np.float16).astype(np.float64)
+    W = (rng.standard_normal((256, 64)) / 8).astype(np.float16).astype(np.float64)
+    prm = orc.Params()
+    Yref = X @ W.T
+    Y, ev, dg = orc.ftgemm(X, W, prm)
+    assert ev == [] and dg["res_max"] < 0.05        # fault-free residuals sit far below the threshold
+    # a flip of mantissa bit 2 changes the element by about 2^-21 of its size: below the threshold
+    Y, ev, _ = orc.ftgemm(X, W, prm, [(3, 10, 2)])
+    assert ev == []
+    # a flip of the top mantissa bit changes it by a quarter to a half of its size: flagged, repaired
+    Y, ev, _ = orc.ftgemm(X, W, prm, [(3, 10, 22)])
+    assert ev == [(3, 10, 1)]
+    assert np.max(np.abs(Y - Yref)) < 1e-5
