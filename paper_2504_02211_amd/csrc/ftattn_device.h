@@ -247,7 +247,7 @@ __global__ __launch_bounds__(256) void ftattn_encode_v(const void* __restrict__ 
 
 // clears the event counter, the recheck counter and the residual maxima (a fill kernel rather
 // than a memset so that a caller may capture the forward call in a graph)
-__global__ void ftattn_reset(int32_t* ev_count, unsigned long long* recheck, uint32_t* resmax, int n_resmax) {
+static __global__ void ftattn_reset(int32_t* ev_count, unsigned long long* recheck, uint32_t* resmax, int n_resmax) {
   int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i == 0) { *ev_count = 0; *recheck = 0ull; }
   if (i < n_resmax) resmax[i] = 0u;

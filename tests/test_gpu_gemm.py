@@ -1,0 +1,170 @@
+"""Parity of the fault-tolerant linear layer (strided ABFT on Y = X W^T, Section 3.3 of the
+paper) between the HIP library, called through its C ABI, and the CPU oracle.
+
+Tolerances.  The kernel accumulates in fp32 over k <= 4096 terms of size <= |x||w|; with inputs
+x ~ N(0,1), w ~ N(0,1/k) the outputs are of order one and the accumulation error is of order
+sqrt(k) * 2^-24 ~ 4e-6, so fp32 results are compared at 1e-4 (absolute, outputs of order one);
+fp16 results carry their own rounding, 2^-11 relative.  Events (row, column, action) are compared
+exactly."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import ftgemm_oracle as orc
+from paper_2504_02211_amd import ftgemm, synth
+
+pytestmark = pytest.mark.gpu
+
+TOL32 = 1e-4
+
+
+def dev16(bits):
+    return torch.from_numpy(bits.view(np.int16)).to("cuda").view(torch.float16)
+
+
+def run(xb, wb, ft_mode, out_dtype=ftgemm.F32, faults=None, encode=True, **kw):
+    m, k = xb.shape
+    n = wb.shape[0]
+    ctx = ftgemm.FtGemm(m, n, k, out_dtype=out_dtype, ft_mode=ft_mode, **kw)
+    x, w = dev16(xb), dev16(wb)
+    y = torch.full((m, n), float("nan"), dtype=torch.float32 if out_dtype == ftgemm.F32 else torch.float16, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    if encode:
+        ctx.encode_weights(w, st)
+    ctx.forward(x, w, y, faults, st)
+    rep = ctx.report()
+    cfg = ctx.config
+    ctx.close()
+    return y.double().cpu().numpy(), rep, cfg
+
+
+def f64(bits):
+    return synth.bits_to_f64(bits, synth.F16)
+
+
+SHAPES = [(256, 256, 64), (300, 520, 128), (515, 777, 192), (1024, 1024, 512), (33, 9, 64), (1, 1, 64)]
+
+
+@pytest.mark.parametrize("m,n,k", SHAPES)
+@pytest.mark.parametrize("ft_mode", [ftgemm.FT_OFF, ftgemm.FT_CORRECT])
+def test_fault_free_output_matches_the_definition(m, n, k, ft_mode):
+    print(f"[gemm clean] m={m} n={n} k={k} ft={ft_mode}", flush=True)
+    xb, wb = synth.gen_linear(m, n, k, synth.LINEAR_SEED_BASE + m)
+    want = orc.linear_clean(f64(xb), f64(wb))
+    got, rep, _ = run(xb, wb, ft_mode)
+    assert np.isfinite(got).all()
+    assert np.abs(got - want).max() <= TOL32
+    assert rep.n_events == 0 and rep.n_events_dropped == 0
+    if ft_mode != ftgemm.FT_OFF and n >= 8:
+        assert 0.0 < rep.residual_max < 0.25      # fault-free residuals sit well below the threshold
+
+
+def test_fp16_output():
+    xb, wb = synth.gen_linear(300, 520, 128, synth.LINEAR_SEED_BASE + 1)
+    want = orc.linear_clean(f64(xb), f64(wb))
+    got, rep, _ = run(xb, wb, ftgemm.FT_CORRECT, out_dtype=ftgemm.F16)
+    assert np.all(np.abs(got - want) <= 2.0 ** -10 * np.maximum(1.0, np.abs(want)))
+    assert rep.n_events == 0
+
+
+def select_faults(X, W, prm, n_faults, seed, bit_lo, bit_hi):
+    """One robust fault per row: the oracle's decision for it must not hinge on rounding."""
+    m, n = X.shape[0], W.shape[0]
+    accepted, rows = [], set()
+    for slot in range(n_faults):
+        stream = synth.linear_fault_stream(seed, slot, m, n, bit_lo, bit_hi)
+        for _ in range(200):
+            r, c, b = next(stream)
+            if r in rows:
+                continue
+            _, _, dg = orc.ftgemm(X[r:r + 1], W, prm, [(0, c, b)])
+            if orc.fault_is_robust(dg) and not orc.fp32_is_fragile(dg["flipped"][0]):
+                accepted.append((r, c, b))
+                rows.add(r)
+                break
+        else:
+            raise RuntimeError(f"no robust fault for slot {slot}")
+    return np.asarray(accepted, np.int32)
+
+
+@pytest.mark.parametrize("m,n,k,bits", [(512, 768, 256, (20, 30)), (300, 520, 128, (0, 31)), (515, 777, 192, (10, 31))])
+def test_injected_faults_are_detected_located_and_repaired_as_the_oracle_says(m, n, k, bits):
+    print(f"[gemm faults] m={m} n={n} k={k} bits={bits}", flush=True)
+    xb, wb = synth.gen_linear(m, n, k, synth.LINEAR_SEED_BASE + 2)
+    X, W = f64(xb), f64(wb)
+    prm = orc.Params()
+    faults = select_faults(X, W, prm, 32, synth.LINEAR_SEED_BASE + 3, *bits)
+    clean_rows = np.setdiff1d(np.arange(0, m, 37), faults[:, 0])
+    rows = np.concatenate([faults[:, 0], clean_rows])
+    local = [(i, int(f[1]), int(f[2])) for i, f in enumerate(faults)]
+    for mode, correct in ((ftgemm.FT_CORRECT, True), (ftgemm.FT_DETECT, False)):
+        prm.correct = correct
+        want, ev, _ = orc.ftgemm(X[rows], W, prm, local)
+        got, rep, cfg = run(xb, wb, mode, faults=faults)
+        assert cfg.tau_rel == np.float32(prm.tau_rel) and cfg.block_n == prm.block_n
+        ev_global = sorted((int(rows[r]), c, a) for (r, c, a) in ev)
+        assert rep.event_list() == ev_global
+        assert len(ev_global) > 0
+        g, w_ = got[rows], want
+        fin = np.isfinite(w_)
+        assert np.array_equal(np.isfinite(g), fin)
+        # damaged values left in place (detect-only, or flips below the threshold) differ from the
+        # oracle's by what the flip does to the last bits of two different roundings of the same sum
+        assert np.all(np.abs(g[fin] - w_[fin]) <= TOL32 * np.maximum(1.0, np.abs(w_[fin])))
+        if correct:
+            harmful = [e for e in ev_global if e[2] == 1]
+            assert len(harmful) == len(ev_global)          # every located fault was repaired
+            ref = orc.linear_clean(X[rows], W)
+            flagged_rows = {r for (r, _, _) in ev_global}
+            sel = np.array([rr in flagged_rows for rr in rows])
+            assert np.abs(g[sel] - ref[sel]).max() <= TOL32
+
+
+def test_unprotected_run_shows_the_damage():
+    xb, wb = synth.gen_linear(256, 256, 128, synth.LINEAR_SEED_BASE + 4)
+    want = orc.linear_clean(f64(xb), f64(wb))
+    faults = np.array([[17, 100, 30], [200, 3, 29]], np.int32)
+    got, rep, _ = run(xb, wb, ftgemm.FT_OFF, faults=faults)
+    assert rep.n_events == 0
+    for r, c, b in faults.tolist():
+        d = orc.bitflip32(want[r, c], b)
+        assert not np.isfinite(d) and not np.isfinite(got[r, c]) or abs(got[r, c] - d) <= 1e-3 * abs(d)
+    got[faults[:, 0], faults[:, 1]] = want[faults[:, 0], faults[:, 1]]
+    assert np.abs(got - want).max() <= TOL32
+
+
+def test_forward_without_encoded_weights_is_refused():
+    xb, wb = synth.gen_linear(256, 256, 64, 5)
+    with pytest.raises(ftgemm.FtGemmError) as ei:
+        run(xb, wb, ftgemm.FT_CORRECT, encode=False)
+    assert ei.value.code == ftgemm.ESTATE
+    with pytest.raises(ftgemm.FtGemmError) as ei:
+        run(xb, wb, ftgemm.FT_CORRECT, faults=np.array([[0, 256, 3]], np.int32))
+    assert ei.value.code == ftgemm.EINVAL
+
+
+def test_feed_forward_size_on_sampled_rows():
+    """The benchmark configuration (16384 tokens, hidden 4096 -> 16384 features), checked on rows
+    the oracle computes one by one, with a handful of injected faults."""
+    m, n, k = 16384, 16384, 4096
+    print(f"[gemm full size] m={m} n={n} k={k}", flush=True)
+    xb, wb = synth.gen_linear(m, n, k, synth.LINEAR_SEED_BASE + 5)
+    rng = np.random.default_rng(11)
+    rows = np.sort(rng.choice(m, size=12, replace=False))
+    X, W = f64(xb[rows]), f64(wb)
+    prm = orc.Params()
+    local = []
+    for i in range(6):
+        for _ in range(50):
+            c, b = int(rng.integers(n)), int(rng.integers(20, 31))
+            _, _, dg = orc.ftgemm(X[i:i + 1], W, prm, [(0, c, b)])
+            if orc.fault_is_robust(dg) and not orc.fp32_is_fragile(dg["flipped"][0]):
+                local.append((i, c, b))
+                break
+    faults = np.array([(int(rows[i]), c, b) for (i, c, b) in local], np.int32)
+    want, ev, dg = orc.ftgemm(X, W, prm, local)
+    got, rep, _ = run(xb, wb, ftgemm.FT_CORRECT, out_dtype=ftgemm.F16, faults=faults)
+    assert rep.event_list() == sorted((int(rows[r]), c, a) for (r, c, a) in ev)
+    assert np.all(np.abs(got[rows] - want) <= 2.0 ** -10 * np.maximum(1.0, np.abs(want)))
+    assert rep.residual_max < 0.5

@@ -7,23 +7,25 @@ import re
 import numpy as np
 import pytest
 
-from paper_2504_02211_amd import ftattn, synth
+from paper_2504_02211_amd import ftattn, ftgemm, synth
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def _declared_functions():
-    text = open(os.path.join(ROOT, "include", "ftattn.h")).read()
+def _declared_functions(header, prefix):
+    text = open(os.path.join(ROOT, "include", header)).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(ftattn_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(" + prefix + r"_[a-z_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol():
     lib = ftattn.load_library()
-    names = _declared_functions()
-    assert set(names) == set(ftattn.EXPORTS)
-    for n in names:
-        assert hasattr(lib, n), n
+    for header, prefix, exports in (("ftattn.h", "ftattn", ftattn.EXPORTS), ("ftgemm.h", "ftgemm", ftgemm.EXPORTS)):
+        names = _declared_functions(header, prefix)
+        assert set(names) == set(exports)
+        for n in names:
+            assert hasattr(lib, n), n
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["ftattn.h", "ftgemm.h"]
 
 
 def test_struct_layouts_match_header():
@@ -56,6 +58,47 @@ def test_create_rejects_bad_configs_without_a_device():
     assert lib.ftattn_forward(None, None, None, None, None, None, 0, None) == ftattn.EINVAL
     assert lib.ftattn_report(None, None) == ftattn.EINVAL
     assert lib.ftattn_destroy(None) == ftattn.EINVAL
+
+
+def test_gemm_create_rejects_bad_configs_without_a_device():
+    lib = ftgemm.load_library()
+    assert C.sizeof(ftgemm.Config) == 13 * 4 and C.sizeof(ftgemm.Fault) == 12
+    assert C.sizeof(ftgemm.Event) == 16 == ftgemm.EVENT_DTYPE.itemsize
+    def create(**kw):
+        base = dict(struct_size=C.sizeof(ftgemm.Config), m=256, n=256, k=128, in_dtype=0, out_dtype=2, ft_mode=1,
+                    stride=8, block_n=0, tau_rel=0.0, tau_abs=-1.0, max_events=0, device=0)
+        base.update(kw)
+        cfg = ftgemm.Config(**base)
+        h = C.c_void_p()
+        rc = lib.ftgemm_create(C.byref(cfg), C.byref(h))
+        return rc, lib.ftgemm_last_error(None).decode()
+    assert create(struct_size=8)[0] == ftgemm.EINVAL
+    assert create(m=0)[0] == ftgemm.EINVAL
+    assert create(k=96)[0] == ftgemm.EUNSUPPORTED
+    assert create(k=0)[0] == ftgemm.EUNSUPPORTED
+    assert create(in_dtype=1)[0] == ftgemm.EUNSUPPORTED
+    assert create(out_dtype=1)[0] == ftgemm.EINVAL
+    assert create(stride=4)[0] == ftgemm.EUNSUPPORTED
+    assert create(ft_mode=3)[0] == ftgemm.EINVAL
+    rc, msg = create(block_n=128)
+    assert rc == ftgemm.EUNSUPPORTED and "block_n" in msg
+    assert lib.ftgemm_forward(None, None, None, None, None, 0, None) == ftgemm.EINVAL
+    assert lib.ftgemm_encode_weights(None, None, None) == ftgemm.EINVAL
+    assert lib.ftgemm_report(None, None) == ftgemm.EINVAL
+    assert lib.ftgemm_destroy(None) == ftgemm.EINVAL
+
+
+def test_linear_inputs_are_deterministic():
+    x1, w1 = synth.gen_linear(300, 520, 128, 7)
+    x2, w2 = synth.gen_linear(300, 520, 128, 7)
+    assert np.array_equal(x1, x2) and np.array_equal(w1, w2)
+    xf, wf = synth.bits_to_f64(x1, synth.F16), synth.bits_to_f64(w1, synth.F16)
+    assert abs(xf.std() - 1) < 0.05 and abs(wf.std() * np.sqrt(128) - 1) < 0.05
+    s = synth.linear_fault_stream(3, 0, 300, 520, 20, 30)
+    a = [next(s) for _ in range(50)]
+    s = synth.linear_fault_stream(3, 0, 300, 520, 20, 30)
+    assert a == [next(s) for _ in range(50)]
+    assert all(0 <= r < 300 and 0 <= c < 520 and 20 <= b <= 30 for r, c, b in a)
 
 
 def test_synth_is_deterministic_and_exact():
