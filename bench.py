@@ -98,6 +98,99 @@ def cpu_baseline(w, q, k, v, n_heads=4):
                       f"Algorithm 1 in fp64, {dt:.1f} s; rate counts one pass of useful flops"}
 
 
+def linear_traffic():
+    """HBM bytes per launch of the FT linear kernel from the committed rocprofv3 counter summary (None if absent)."""
+    path = os.path.join(ROOT, "profiles", "ftgemm_main_ffn_16k_16k_4k_counters.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch_ft"):
+            return float(line.split("=")[1])
+    return None
+
+
+def bench_linear(args):
+    """The protected feed-forward GEMM (strided ABFT on Y = X W^T): one step = one ftgemm_forward on
+    resident operands; the checksums of the (static) weights are encoded once, outside the step."""
+    import numpy as np
+    import torch
+    from paper_2504_02211_amd import ftgemm, synth
+    m, n, k = 16384, 16384, 4096
+    xb, wb = synth.gen_linear(m, n, k, synth.LINEAR_SEED_BASE + 5)
+    dev = lambda b: torch.from_numpy(b.view(np.int16)).cuda().view(torch.float16)
+    x, w = dev(xb), dev(wb)
+    y = torch.empty((m, n), dtype=torch.float16, device="cuda")
+    flops = 2.0 * m * n * k
+    res = {}
+    for name, mode in (("ft", ftgemm.FT_CORRECT), ("off", ftgemm.FT_OFF)):
+        ctx = ftgemm.FtGemm(m, n, k, out_dtype=ftgemm.F16, ft_mode=mode)
+        stream = torch.cuda.Stream()
+        sp = stream.cuda_stream
+        ctx.set_timing(True)
+        ctx.encode_weights(w, sp)
+        for _ in range(args.warmup):
+            ctx.forward(x, w, y, None, sp)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ctx.set_timing(False)
+        with torch.cuda.stream(stream):
+            e0.record(stream)
+            for _ in range(args.steps):
+                ctx.forward(x, w, y, None, sp)
+            e1.record(stream)
+        torch.cuda.synchronize()
+        ms_step = e0.elapsed_time(e1) / args.steps
+        ctx.set_timing(True)
+        ks = []
+        for _ in range(min(args.steps, 10)):
+            ctx.forward(x, w, y, None, sp)
+            ks.append(ctx.get_timing())
+        rep = ctx.report()
+        res[name] = dict(ms_step=ms_step, ms_kernel=sum(ks) / len(ks), events=rep.n_events, resmax=rep.residual_max)
+        ctx.close()
+    ft, un = res["ft"], res["off"]
+    tf = flops / ft["ms_step"] / 1e9
+    tfk = flops / ft["ms_kernel"] / 1e9
+    out = {"metric": "FT-linear (strided ABFT GEMM) TFLOP/s at 1 GPU, % overhead vs unprotected, % MFMA peak",
+           "value": round(tf, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": round(ft["ms_step"], 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f16", "data": "synthetic",
+           "config": {"workload": f"feed-forward up-projection: {m} tokens, {k} -> {n} features, fp16 in, fp16 out, "
+                                  f"fault-free", "block_n": 256, "stride": 8},
+           "unprotected_tflops": round(flops / un["ms_step"] / 1e9, 2),
+           "unprotected_ms_per_step": round(un["ms_step"], 4),
+           "ft_overhead_pct": round((ft["ms_step"] / un["ms_step"] - 1) * 100, 2),
+           "ms_kernel": round(ft["ms_kernel"], 4), "ms_kernel_unprotected": round(un["ms_kernel"], 4),
+           "events": ft["events"], "residual_max": round(ft["resmax"], 5),
+           "roofline": {"bound": "mfma", "achieved": round(tfk, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                        "frac": round(tfk / MFMA_PEAK_TFLOPS, 4), "traffic": linear_traffic(),
+                        "kernel": "ftgemm_main (FT linear layer)", "algorithmic_flops_per_launch": flops}}
+    if args.pmc_copy:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["pmc_copy_bytes_each_way"] = src.numel() * 4
+    if not args.no_cpu_baseline:
+        from oracle import ftgemm_oracle as orc
+        rows = 256
+        X, W = synth.bits_to_f64(xb[:rows], synth.F16), synth.bits_to_f64(wb, synth.F16)
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p_.get("num_threads", 1) for p_ in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        t0 = time.perf_counter()
+        orc.ftgemm(X, W, orc.Params())
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(2.0 * rows * n * k / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores),
+                               "kind": "oracle", "sample": f"the first {rows} token rows of the same workload through the "
+                               f"fp64 oracle (product, checksum products, verification), {dt:.1f} s; useful flops only"}
+    print(json.dumps(out))
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -107,6 +200,8 @@ def main():
     ap.add_argument("--block-m", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all-workloads", action="store_true", help="also time workloads 2-4 (extra keys)")
+    ap.add_argument("--linear", action="store_true",
+                    help="time the protected feed-forward GEMM instead of attention (its own JSON line)")
     ap.add_argument("--pmc-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (calibration of HBM byte counters under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -114,6 +209,9 @@ def main():
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
               "(the path shards over batch*heads and row tiles without communication, see DESIGN.md)", file=sys.stderr)
         return 2
+
+    if args.linear:
+        return bench_linear(args)
 
     import torch
     from paper_2504_02211_amd import ftattn, synth

@@ -67,7 +67,7 @@ extern "C" int ftgemm_create(const ftgemm_config* cfg, ftgemm_ctx** out) {
   *out = nullptr;
   if (cfg->struct_size != sizeof(ftgemm_config)) return gfail(nullptr, FTGEMM_EINVAL, "struct_size mismatch");
   if (cfg->m < 1 || cfg->n < 1) return gfail(nullptr, FTGEMM_EINVAL, "m and n must be >= 1");
-  if (cfg->k < GBK || cfg->k % GBK != 0) return gfail(nullptr, FTGEMM_EUNSUPPORTED, "k must be a positive multiple of 64");
+  if (cfg->k < 64 || cfg->k % 64 != 0) return gfail(nullptr, FTGEMM_EUNSUPPORTED, "k must be a positive multiple of 64");
   if (cfg->in_dtype != FTGEMM_F16) return gfail(nullptr, FTGEMM_EUNSUPPORTED, "in_dtype must be F16");
   if (cfg->out_dtype != FTGEMM_F32 && cfg->out_dtype != FTGEMM_F16) return gfail(nullptr, FTGEMM_EINVAL, "out_dtype must be F32 or F16");
   if (cfg->ft_mode < 0 || cfg->ft_mode > 2) return gfail(nullptr, FTGEMM_EINVAL, "ft_mode out of range");
@@ -181,7 +181,7 @@ extern "C" int ftgemm_forward(ftgemm_ctx* c, const void* x, const void* w, void*
   a.resmax = c->d_resmax;
   gemm_fn f = select_gemm(ft, n_faults > 0);
   if (c->timing) GHIP_TRY(c, hipEventRecord(c->ev[0], st));
-  hipLaunchKernelGGL(f, dim3(c->Tm * c->Tn), dim3(512), gemm_lds(ft), st, a);
+  hipLaunchKernelGGL(f, dim3(c->Tm * c->Tn), dim3(GWAVES * 64), gemm_lds(ft), st, a);
   GHIP_TRY(c, hipGetLastError());
   if (c->timing) GHIP_TRY(c, hipEventRecord(c->ev[1], st));
   c->last_stream = st;

@@ -37,6 +37,7 @@ constexpr int GBN = 256;      // output features per workgroup tile = one checks
 constexpr int GBK = 64;       // K step
 constexpr int GCK = 32;       // checksum rows per block: {c1 hi, c1 lo, c2 hi, c2 lo} x 8 classes
 constexpr int GFOLD = GBN / 8;
+constexpr int GWAVES = 8;     // waves per workgroup
 constexpr int ROWB = GBK * 2; // bytes per tile row in LDS
 
 struct GFault { int32_t row, col, bit; };
@@ -120,7 +121,7 @@ __device__ __forceinline__ void log_gemm_event(const GArgs& a, int row, int col,
 }
 
 template <bool FT, bool INJ>
-__global__ __launch_bounds__(512) void ftgemm_main(const GArgs a) {
+__global__ __launch_bounds__(GWAVES * 64) void ftgemm_main(const GArgs a) {
   using S = GStage<FT>;
   constexpr int NA = FT ? 9 : 8;          // A operands (32-row blocks of W, + the checksum block) per k-step
   constexpr int NKS = GBK / 16;           // k-steps of 16 per stage
@@ -218,8 +219,8 @@ __global__ __launch_bounds__(512) void ftgemm_main(const GArgs a) {
 #pragma unroll
     for (int k = 0; k < NOPS; ++k) {
       if (k + RING - 1 < NOPS) buf[(k + RING - 1) % RING] = load_op(k + RING - 1);
-      // the next stage is fetched one piece every four MFMAs
-      if (k % 4 == 1 && k / 4 < S::NLOAD) issue_piece(k / 4, kb + 1, st ^ 1, more);
+      // the next stage is requested at the start of this one: its latency budget is one K step
+      if (k < S::NLOAD) issue_piece(k, kb + 1, st ^ 1, more);
       const half8 av = buf[k % RING];
       const int ks = k / NA, y = k % NA;
       if (y < 8) acc[y] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, xf[ks], acc[y], 0, 0, 0);
