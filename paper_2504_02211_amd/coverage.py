@@ -15,9 +15,14 @@ its lower bound included).  Every flip hits its own query row, so a detection is
 fault by (batch, head, row).  A fault counts as harmful when, left alone, it moves some output of
 its row by more than the parity tolerance of the library (2e-3).
 
+A second mode (``--ber``) injects flips at a given rate per computed fp32 intermediate with no
+constraint on where they fall, and counts the rows that are wrong without protection, flagged
+under protection, and right again after correction.
+
 Everything here goes through the C ABI; the inputs are synthetic and seeded.
 
     python -m paper_2504_02211_amd.coverage --seq 2048 --heads 8 --faults-per-head 48
+    python -m paper_2504_02211_amd.coverage --seq 2048 --heads 8 --ber 1e-7 1e-6 1e-5 1e-4
 """
 from __future__ import annotations
 
@@ -153,6 +158,89 @@ def sweep(q: np.ndarray, k: np.ndarray, v: np.ndarray, dtype: int, causal: bool,
     return result
 
 
+def population(batch: int, heads: int, seq: int, head_dim: int, causal: bool, block_n: int) -> int:
+    """Number of fp32 intermediates the injector can hit: raw scores and exponentials of every
+    unmasked position, one row-sum and head_dim output accumulators per (row, key-tile iteration)."""
+    scores = seq * (seq + 1) // 2 if causal else seq * seq
+    iters = sum(synth.n_kv_tiles(r, seq, block_n, causal) for r in range(seq))
+    return batch * heads * (2 * scores + iters * (1 + head_dim))
+
+
+def draw_ber_faults(batch: int, heads: int, seq: int, head_dim: int, causal: bool, block_n: int, ber: float,
+                    seed: int, limit: int = 60000) -> np.ndarray:
+    """round(ber * population) single-bit flips (at least one, at most `limit`) at seeded positions
+    spread evenly over the heads, with no constraint on how they fall: several may share a row, a
+    key tile or a checksum class (the bit-error-rate experiments of Section 4.2)."""
+    n = int(min(limit, max(1, round(ber * population(batch, heads, seq, head_dim, causal, block_n)))))
+    stages = (synth.ST_S, synth.ST_EXP, synth.ST_ROWSUM, synth.ST_OACC)
+    streams = {}
+    out: List[Tuple[int, ...]] = []
+    for i in range(n):
+        bh = i % (batch * heads)
+        b, h = divmod(bh, heads)
+        if bh not in streams:
+            streams[bh] = synth.candidate_stream(seed, b, h, 0, seq, head_dim, block_n, causal, stages, 0, 30)
+        out.append(next(streams[bh]))
+    return synth.faults_to_array(out)
+
+
+def ber_sweep(q: np.ndarray, k: np.ndarray, v: np.ndarray, dtype: int, causal: bool, bers: Sequence[float],
+              seed: int) -> List[Dict[str, object]]:
+    """For every bit error rate: how many rows the flips damage when nothing protects them, how
+    many of those rows raise an event under protection, and how many are back within the
+    tolerance after correction (default thresholds)."""
+    r = Runner(q, k, v, dtype, causal)
+    B, H, N, d = q.shape
+    clean, _, cfg = r.run(None, ftattn.FT_OFF)
+    rows_out = []
+    for ber in bers:
+        faults = draw_ber_faults(B, H, N, d, causal, cfg.block_n, ber, seed)
+        damaged, _, _ = r.run(faults, ftattn.FT_OFF)
+        fixed, rep, _ = r.run(faults, ftattn.FT_CORRECT)
+        with np.errstate(all="ignore"):
+            dmg = np.abs(damaged - clean).max(axis=-1)
+            left = np.abs(fixed - clean).max(axis=-1)
+        dmg = np.where(np.isfinite(dmg), dmg, np.inf)
+        left = np.where(np.isfinite(left), left, np.inf)
+        harmful = dmg > HARM_TOL                                   # [B, H, N] rows
+        flagged = np.zeros_like(harmful)
+        e = rep.events
+        flagged[e["b"], e["h"], e["row"]] = True
+        hit = np.zeros_like(harmful)
+        hit[faults[:, 0], faults[:, 1], faults[:, 4]] = True
+        rows_out.append({
+            "ber": float(ber), "faults": int(len(faults)), "rows_hit": int(hit.sum()),
+            "rows_harmed": int(harmful.sum()), "harmed_flagged": int((harmful & flagged).sum()),
+            "harmed_repaired": int((harmful & (left <= HARM_TOL)).sum()),
+            "rows_bad_after": int((left > HARM_TOL).sum()),
+            "flagged_unharmed_hit": int((flagged & ~harmful & hit).sum()),
+            "flagged_not_hit": int((flagged & ~hit).sum()),
+            "events": int(rep.n_events), "events_dropped": int(rep.n_events_dropped),
+            "rows_bad_after_by_stage": {synth.STAGE_NAMES[st]: int(((left > HARM_TOL) & _rows_of(faults, st, harmful.shape)).sum())
+                                         for st in range(4)},
+        })
+    return rows_out
+
+
+def _rows_of(faults: np.ndarray, stage: int, shape) -> np.ndarray:
+    m = np.zeros(shape, bool)
+    f = faults[faults[:, 2] == stage]
+    m[f[:, 0], f[:, 1], f[:, 4]] = True
+    return m
+
+
+def ber_markdown(rows: List[Dict[str, object]]) -> str:
+    out = ["| bit error rate | flips | rows harmed (unprotected) | of those flagged | of those repaired | rows still wrong "
+           "(by stage of a flip in the row: S / EXP / ROWSUM / OACC) | events on rows no flip hit |", "|---|---|---|---|---|---|---|"]
+    for r in rows:
+        st = r["rows_bad_after_by_stage"]
+        pct = lambda a, b: f"{a} ({100.0 * a / b:.1f} %)" if b else f"{a}"
+        out.append(f"| {r['ber']:.0e} | {r['faults']} | {r['rows_harmed']} | {pct(r['harmed_flagged'], r['rows_harmed'])} | "
+                   f"{pct(r['harmed_repaired'], r['rows_harmed'])} | {r['rows_bad_after']} ({st['S']} / {st['EXP']} / "
+                   f"{st['ROWSUM']} / {st['OACC']}) | {r['flagged_not_hit']} |")
+    return "\n".join(out)
+
+
 def to_markdown(res: Dict[str, object]) -> str:
     names = {"product": "product-form check, threshold eps1 (flips of S and exp)",
              "sum": "sum-form check of O, threshold tau_o (flips of the output accumulator)",
@@ -183,10 +271,19 @@ def main() -> None:
     ap.add_argument("--non-causal", action="store_true")
     ap.add_argument("--faults-per-head", type=int, default=48)
     ap.add_argument("--seed", type=lambda s: int(s, 0), default=0xC0FE)
+    ap.add_argument("--ber", type=float, nargs="*", default=None,
+                    help="run the bit-error-rate sweep at these rates instead of the threshold sweep")
     args = ap.parse_args()
     dtype = synth.F16 if args.dtype == "fp16" else synth.BF16
     shape = (args.batch, args.heads, args.seq, args.head_dim)
     q, k, v = synth.gen_qkv(shape, dtype, args.seed)
+    if args.ber is not None:
+        bers = args.ber or [1e-7, 1e-6, 1e-5, 1e-4]
+        print(f"workload: batch {args.batch}, heads {args.heads}, seq {args.seq}, head_dim {args.head_dim}, {args.dtype}, "
+              f"{'non-causal' if args.non_causal else 'causal'}, N(0,1) inputs, seed {args.seed:#x}; "
+              f"{population(*shape, not args.non_causal, 64)} fp32 intermediates per pass")
+        print(ber_markdown(ber_sweep(q, k, v, dtype, not args.non_causal, bers, args.seed + 2)))
+        return
     faults = draw_faults(*shape, not args.non_causal, 64, args.faults_per_head, args.seed + 1)
     res = sweep(q, k, v, dtype, not args.non_causal, faults)
     print(f"workload: batch {args.batch}, heads {args.heads}, seq {args.seq}, head_dim {args.head_dim}, {args.dtype}, "

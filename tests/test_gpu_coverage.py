@@ -54,3 +54,39 @@ def test_sweep_shape_and_oracle_agreement():
             mine = {e for e in got if e[0] == b and e[1] == h and e[4] == row}
             assert mine == {(b, h) + e for e in ev}, (fam, tuple(f), sorted(mine), ev)
         assert compared >= 24, compared
+
+
+def test_bit_error_rate_sweep():
+    """Unconstrained flips at two rates: no event on a row that no flip hit; at the low rate (flips on
+    separate rows) every row that is still wrong after correction carries a row-sum flip (the range
+    restriction is the weak check), and the events of every hit row equal the oracle's."""
+    shape = (1, 2, 640, 64)
+    dtype, causal = synth.F16, True
+    q, k, v = synth.gen_qkv(shape, dtype, 0xC0FE)
+    rows = coverage.ber_sweep(q, k, v, dtype, causal, (2e-5, 1e-3), 0xBE7)
+    print(coverage.ber_markdown(rows), flush=True)
+    lo, hi = rows
+    assert lo["faults"] >= 8 and hi["faults"] > 20 * lo["faults"]
+    for r in rows:
+        assert r["flagged_not_hit"] == 0 and r["events_dropped"] == 0
+        assert r["harmed_flagged"] >= 0.6 * r["rows_harmed"] > 0
+    st = lo["rows_bad_after_by_stage"]
+    assert lo["rows_bad_after"] == st["ROWSUM"]
+
+    faults = coverage.draw_ber_faults(*shape, causal, 64, 2e-5, 0xBE7)
+    r = coverage.Runner(q, k, v, dtype, causal)
+    _, rep, cfg = r.run(faults, ftattn.FT_CORRECT)
+    prm = H.oracle_params(shape[2], shape[3], causal, block_n=cfg.block_n, scale=cfg.softmax_scale,
+                          eps1=cfg.eps1, tau_o=cfg.tau_o, delta_l=cfg.delta_l)
+    got = rep.event_set()
+    compared = 0
+    for (b, h, row) in sorted({(int(f[0]), int(f[1]), int(f[4])) for f in faults}):
+        fl = [tuple(int(x) for x in f[2:]) for f in faults if (int(f[0]), int(f[1]), int(f[4])) == (b, h, row)]
+        Q, K, V = H.head_f64(q, dtype, b, h), H.head_f64(k, dtype, b, h), H.head_f64(v, dtype, b, h)
+        _, ev, dg = orc.efta_rows(Q[row:row + 1], np.array([row]), K, V, prm, fl)
+        if not orc.fault_is_robust(dg) or any(orc.fp32_is_fragile(x, st_) for st_, x in dg["flipped"]):
+            continue
+        compared += 1
+        mine = {e for e in got if e[0] == b and e[1] == h and e[4] == row}
+        assert mine == {(b, h) + e for e in ev}, (fl, sorted(mine), ev)
+    assert compared >= 5, compared
