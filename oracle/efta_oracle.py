@@ -61,6 +61,18 @@ listed in the design notes of the repository):
 * The softmax scale is applied inside x = scale*S - m; the S stage is the raw
   accumulator.  Thresholds are in logit units / normalised-output units.
 
+* ``rowsum_fold`` (an extension, off by default; the paper's own row-sum protection is the
+  range restriction above).  The row-sum obeys the same recurrence as a column of the output
+  accumulator whose V entries are all one.  With this option the value-tile checksums of class 0
+  are encoded as if V had such a column at feature index d (fold d/s): check1[:,0] += 1,
+  check2[:,0] += d/s + 1 for every real key, so the first checksum of class 0 carries the
+  row-sum through GEMM II and the rescale at no extra cost.  After the loop the row-sum that
+  the checksum implies, check1[0] - sum of the class-0 output folds, is compared with the
+  accumulated one (relative difference against tau_o); on a mismatch the usual location rule is
+  applied to the d/s + 1 folds, and if it names the extra fold the row-sum is replaced by the
+  implied one (event CHECK_L).  The range restriction is not applied in this mode.  In the final
+  sum-form check the normalised extra fold (row-sum / row-sum = 1) is part of class 0.
+
 Thresholds (eps1, tau_o, delta_l) are this repository's choices: the paper's own
 values (0.48 absolute, 7e-6 relative) belong to its one-word fp16 checksums and
 carry a 5.9% false-alarm rate.  Which faults the paper's code would flag at a
@@ -88,6 +100,8 @@ class Params:
     tau_o: float = 0.75 * 2.0 ** -9    # final sum check, normalised-output units
     delta_l: float = 2.0 ** -10        # relative slack of the row-sum range
     correct: bool = True               # False: detect and locate only
+    rowsum_fold: bool = False          # True: the row-sum rides through GEMM II as an extra fold of
+                                       # checksum class 0 and is verified / repaired exactly (see below)
 
 
 def bitflip32(x: float, bit: int) -> float:
@@ -251,6 +265,9 @@ def efta_rows(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
         # encode (Algorithm 1, "Encode tensor checksum")
         Kc1, Kc2 = encode_k(Kj, s)
         Vc1, Vc2 = encode_v(Vj, s)
+        if prm.rowsum_fold:
+            Vc1[:kv, 0] += 1.0
+            Vc2[:kv, 0] += nV + 1.0
         # GEMM I
         Qa = Q[act]
         S = Qa @ Kj.T
@@ -341,23 +358,46 @@ def efta_rows(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
                 Ot[ri, col] = bitflip32(Ot[ri, col], bit)
         m[act] = m_new
 
-    # range restriction of the row-sum
     U = np.minimum(row_idx + 1, N).astype(np.float64) if prm.causal else np.full(n, float(N))
-    with np.errstate(all="ignore"):
-        in_range = (lower * (1 - prm.delta_l) <= ell) & (ell <= U * (1 + prm.delta_l))
-        dist = np.minimum(np.abs(ell / (lower * (1 - prm.delta_l)) - 1), np.abs(ell / (U * (1 + prm.delta_l)) - 1))
-    dist = np.where(np.isfinite(dist), dist, np.inf)
-    for i in np.flatnonzero(~in_range):
-        events.append((CHECK_L, -1, int(row_idx[i]), 0))
-        if prm.correct:
-            ell[i] = lower[i]
+    l_ratio = 0.0
+    if prm.rowsum_fold:
+        # exact check of the row-sum against the one the class-0 checksum implies
+        dist = np.full(n, np.inf)
+        cols0 = s * np.arange(nV)
+        for i in range(n):
+            x = Ot[i, cols0]
+            with np.errstate(all="ignore"):
+                l_c = Oc1[i, 0] - x.sum()
+                r = (l_c - ell[i]) / l_c
+                ok = np.isfinite(r) and abs(r) <= prm.tau_o
+            l_ratio = max(l_ratio, abs(r) / prm.tau_o if np.isfinite(r) else np.inf)
+            if ok:
+                continue
+            lstar, val = locate_and_restore(np.append(x, ell[i]), Oc1[i, 0], Oc2[i, 0])
+            if lstar == nV:
+                events.append((CHECK_L, -1, int(row_idx[i]), 0))
+                if prm.correct:
+                    ell[i] = val
+    else:
+        # range restriction of the row-sum
+        with np.errstate(all="ignore"):
+            in_range = (lower * (1 - prm.delta_l) <= ell) & (ell <= U * (1 + prm.delta_l))
+            dist = np.minimum(np.abs(ell / (lower * (1 - prm.delta_l)) - 1), np.abs(ell / (U * (1 + prm.delta_l)) - 1))
+        dist = np.where(np.isfinite(dist), dist, np.inf)
+        for i in np.flatnonzero(~in_range):
+            events.append((CHECK_L, -1, int(row_idx[i]), 0))
+            if prm.correct:
+                ell[i] = lower[i]
     # normalisation
     with np.errstate(all="ignore"):
         O = Ot / ell[:, None]
         C1 = Oc1 / ell[:, None]
         C2 = Oc2 / ell[:, None]
+        extra = ell / ell                      # the normalised extra fold of class 0 (rowsum_fold)
         # unified verification of GEMM II, rescale and normalisation
         sum1, _ = fold(O, s)
+        if prm.rowsum_fold:
+            sum1[:, 0] += extra
         R = C1 - sum1
         okO = np.abs(R) <= prm.tau_o
     finR = np.isfinite(R)
@@ -366,12 +406,17 @@ def efta_rows(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
         o_ratio = np.inf
     for (i, c) in zip(*np.nonzero(~okO)):
         cols = c + s * np.arange(nV)
-        lstar, val = locate_and_restore(O[i, cols], C1[i, c], C2[i, c])
+        if prm.rowsum_fold and c == 0:
+            lstar, val = locate_and_restore(np.append(O[i, cols], extra[i]), C1[i, c], C2[i, c])
+            if lstar == nV:
+                continue                       # the row-sum itself: reported by the check above
+        else:
+            lstar, val = locate_and_restore(O[i, cols], C1[i, c], C2[i, c])
         events.append((CHECK_O, -1, int(row_idx[i]), int(cols[lstar]) if lstar >= 0 else -1))
         if prm.correct and lstar >= 0:
             O[i, cols[lstar]] = val
     diag = {"lambda_ratio": float(lam_ratio), "o_ratio": float(o_ratio),
-            "l_distance": float(dist.min()) if n else np.inf, "flipped": flipped}
+            "l_distance": float(dist.min()) if n else np.inf, "l_ratio": float(l_ratio), "flipped": flipped}
     return O, sorted(events), diag
 
 
@@ -382,8 +427,8 @@ def fault_is_robust(diag: Dict[str, float], band: float = 4.0, l_band: float = 2
     statistic is either below threshold/band or above threshold*band, and the
     final row-sum is further than ``l_band`` (relative) from both range bounds.
     """
-    for key in ("lambda_ratio", "o_ratio"):
-        r = diag[key]
+    for key in ("lambda_ratio", "o_ratio", "l_ratio"):
+        r = diag.get(key, 0.0)
         if 1.0 / band <= r <= band:
             return False
     return diag["l_distance"] > l_band

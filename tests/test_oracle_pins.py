@@ -390,3 +390,75 @@ def test_bitflip_and_fragility_helpers():
     assert orc.fault_is_robust({"lambda_ratio": 10.0, "o_ratio": 1e-9, "l_distance": 0.5})
     assert not orc.fault_is_robust({"lambda_ratio": 1.5, "o_ratio": 1e-9, "l_distance": 0.5})
     assert not orc.fault_is_robust({"lambda_ratio": 0.0, "o_ratio": 0.0, "l_distance": 1e-5})
+
+
+# ---------------------------------------------------------------- row-sum as an extra checksum fold
+
+@pytest.mark.parametrize("N,d,Bc,causal", [(128, 64, 64, False), (200, 16, 64, True), (77, 8, 16, False), (1, 8, 8, True)])
+def test_rowsum_fold_is_silent_and_exact_without_faults(N, d, Bc, causal):
+    """A column of ones appended to V accumulates exactly the row-sum (eq. (2)-(8) applied to
+    that column), so the class-0 checksum minus the class-0 output folds equals the row-sum."""
+    Q, K, V = _rand(N, d, 70 + N)
+    prm = Params(scale=d ** -0.5, causal=causal, block_n=Bc, rowsum_fold=True)
+    O, ev, dg = efta_rows(Q, np.arange(N), K, V, prm)
+    assert ev == []
+    assert np.abs(O - attention_clean(Q, K, V, prm.scale, causal)).max() < 1e-12
+    assert dg["l_ratio"] < 1e-9 and dg["o_ratio"] < 1e-9 and dg["lambda_ratio"] < 1e-9
+
+
+def test_rowsum_fold_repairs_every_harmful_rowsum_flip():
+    """Every bit of the row-sum, at several rows and iterations: with the extra fold a flip that
+    changes the output beyond the threshold is named as the row-sum and put right exactly, where
+    the range restriction leaves most of them in place."""
+    N, d, Bc = 96, 16, 32
+    Q, K, V = _rand(N, d, 71)
+    clean = attention_clean(Q, K, V, 0.4, True)
+    exact = Params(scale=0.4, causal=True, block_n=Bc, rowsum_fold=True)
+    ranged = Params(scale=0.4, causal=True, block_n=Bc)
+    left_wrong = 0
+    for row, kt in ((95, 0), (95, 2), (40, 1), (5, 0), (64, 2)):
+        for bit in range(32):
+            f = [(ST_ROWSUM, kt, row, 0, bit)]
+            O, ev, dg = efta_rows(Q[row:row + 1], np.array([row]), K, V, exact, f)
+            if dg["l_ratio"] > 1:
+                assert ev == [(CHECK_L, -1, row, 0)], (row, kt, bit, ev)
+                assert np.abs(O[0] - clean[row]).max() < 1e-10
+            else:
+                assert ev == [] and np.abs(O[0] - clean[row]).max() < 4 * exact.tau_o * np.abs(clean[row]).max() + 1e-12
+            O2, _, _ = efta_rows(Q[row:row + 1], np.array([row]), K, V, ranged, f)
+            left_wrong += bool(np.abs(O2[0] - clean[row]).max() > 1e-3)
+    assert left_wrong > 20          # what the extension is for
+
+
+def test_rowsum_fold_keeps_class0_output_faults_apart():
+    N, d, Bc = 64, 32, 16
+    Q, K, V = _rand(N, d, 72)
+    prm = Params(scale=0.3, causal=True, block_n=Bc, rowsum_fold=True)
+    clean = attention_clean(Q, K, V, 0.3, True)
+    for (row, col, kt, bit) in ((63, 0, 0, 28), (40, 24, 2, 22), (20, 8, 1, 30), (33, 16, 0, 25), (50, 5, 1, 27)):
+        O, ev, dg = efta_rows(Q, np.arange(N), K, V, prm, [(ST_OACC, kt, row, col, bit)])
+        assert ev == [(CHECK_O, -1, row, col)], (row, col, ev)
+        assert np.abs(O - clean).max() < 1e-10
+
+
+def test_rowsum_fold_detect_only_reports_once():
+    N, d, Bc = 64, 16, 16
+    Q, K, V = _rand(N, d, 73)
+    prm = Params(scale=0.3, causal=False, block_n=Bc, rowsum_fold=True, correct=False)
+    clean = attention_clean(Q, K, V, 0.3, False)
+    O, ev, _ = efta_rows(Q, np.arange(N), K, V, prm, [(ST_ROWSUM, 1, 10, 0, 24)])
+    assert ev == [(CHECK_L, -1, 10, 0)]
+    assert np.abs(O[10] - clean[10]).max() > 1e-2
+    O[10] = clean[10]
+    assert np.abs(O - clean).max() < 1e-12
+
+
+def test_rowsum_fold_non_finite_rowsum():
+    N, d, Bc = 32, 8, 16
+    Q, K, V = _rand(N, d, 74)
+    prm = Params(scale=0.3, causal=False, block_n=Bc, rowsum_fold=True)
+    clean = attention_clean(Q, K, V, 0.3, False)
+    for bit in (30, 31):
+        O, ev, _ = efta_rows(Q, np.arange(N), K, V, prm, [(ST_ROWSUM, 1, 7, 0, bit)])
+        assert ev == [(CHECK_L, -1, 7, 0)]
+        assert np.abs(O - clean).max() < 1e-10
