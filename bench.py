@@ -39,9 +39,10 @@ def measured_traffic(cfg: int):
     return None
 
 
-def time_variant(torch, ftattn, w, tq, tk, tv, ft_mode, steps, warmup, block_m):
+def time_variant(torch, ftattn, w, tq, tk, tv, ft_mode, steps, warmup, block_m, rowsum_fold=False):
     o = torch.empty((w.batch, w.heads, w.seq, w.head_dim), dtype=torch.float32, device="cuda")
-    ctx = ftattn.FtAttn(w.batch, w.heads, w.seq, w.head_dim, w.dtype, w.causal, ft_mode=ft_mode, block_m=block_m)
+    ctx = ftattn.FtAttn(w.batch, w.heads, w.seq, w.head_dim, w.dtype, w.causal, ft_mode=ft_mode, block_m=block_m,
+                        rowsum_fold=rowsum_fold)
     stream = torch.cuda.Stream()
     sp = stream.cuda_stream
     for _ in range(warmup):
@@ -200,6 +201,8 @@ def main():
     ap.add_argument("--block-m", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--all-workloads", action="store_true", help="also time workloads 2-4 (extra keys)")
+    ap.add_argument("--rowsum-fold", action="store_true",
+                    help="attention: protect the row-sum as an extra fold of checksum class 0 (exact check) instead of the range restriction")
     ap.add_argument("--linear", action="store_true",
                     help="time the protected feed-forward GEMM instead of attention (its own JSON line)")
     ap.add_argument("--pmc-copy", action="store_true",
@@ -228,7 +231,7 @@ def main():
         w = synth.WORKLOADS[cfg]
         q, k, v = synth.gen_workload(cfg)
         tq, tk, tv = (to_dev(x, w.dtype) for x in (q, k, v))
-        ft = time_variant(torch, ftattn, w, tq, tk, tv, ftattn.FT_CORRECT, args.steps, args.warmup, args.block_m)
+        ft = time_variant(torch, ftattn, w, tq, tk, tv, ftattn.FT_CORRECT, args.steps, args.warmup, args.block_m, args.rowsum_fold)
         un = time_variant(torch, ftattn, w, tq, tk, tv, ftattn.FT_OFF, args.steps, args.warmup, args.block_m)
         results[cfg] = (w, ft, un)
         if cfg == args.workload:
@@ -248,7 +251,8 @@ def main():
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"cfg{w.cfg} {w.name}: batch {w.batch}, heads {w.heads}, seq {w.seq}, head_dim {w.head_dim}, "
                                f"{'bf16' if w.dtype else 'fp16'} in, fp32 out, {'causal' if w.causal else 'non-causal'}, fault-free",
-                   "block_m": ft["block_m"], "block_n": ft["block_n"], "stride": 8},
+                   "block_m": ft["block_m"], "block_n": ft["block_n"], "stride": 8,
+                   "rowsum_protection": "extra checksum fold" if args.rowsum_fold else "range restriction"},
         "unprotected_tflops": round(tf_un, 2), "unprotected_ms_per_step": round(un["ms_step"], 4),
         "ft_overhead_pct": round((ft["ms_step"] / un["ms_step"] - 1) * 100, 2),
         "mfma_peak_pct": round(tf / MFMA_PEAK_TFLOPS * 100, 2),

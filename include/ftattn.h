@@ -79,6 +79,15 @@ typedef struct {
   float tau_o;            /* threshold of the final sum-form check on the normalised output
                              (Algorithm 1, last "if"); <= 0 selects 0.75 * 2^-9 */
   float delta_l;          /* relative slack of the row-sum range check; <= 0 selects 2^-10 */
+  int32_t rowsum_fold;    /* 0: the row-sum is protected by the range restriction of Section 3.4 case 3
+                             (the paper's method).  1 (an extension): the value-tile checksums of class 0
+                             also fold a column of ones at feature index head_dim, so that the first
+                             checksum of class 0 carries the row-sum through GEMM II and the rescale; after
+                             the loop the row-sum it implies is compared with the accumulated one
+                             (relative difference against tau_o), the location rule over the
+                             head_dim/8 + 1 folds decides whether the row-sum is the wrong element, and
+                             if so it is replaced by the implied one (event FTATTN_CHECK_L).  The range
+                             restriction is not applied in this mode. */
   int32_t max_events;     /* capacity of the event log; <= 0 selects 65536 */
   int32_t device;         /* HIP device ordinal */
 } ftattn_config;
@@ -112,7 +121,8 @@ typedef struct {
   const uint8_t* rowtile_flags;  /* [batch, heads, tiles_m], FTATTN_RF_* */
   const float* residual_max;     /* [batch, heads, tiles_m, 4]: largest fault-free-looking statistic seen:
                                     0: |prod/expected - 1| of the product check, 1: |sum residual| of the
-                                    O check, 2: row-sum / upper bound, 3: lower bound / row-sum */
+                                    O check, 2: row-sum / upper bound (rowsum_fold: relative row-sum
+                                    residual), 3: lower bound / row-sum */
   int64_t recheck_entries;    /* how often a wave left the fast path to re-evaluate a check exactly */
 } ftattn_report_view;
 

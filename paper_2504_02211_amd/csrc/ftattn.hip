@@ -101,6 +101,7 @@ extern "C" int ftattn_create(const ftattn_config* cfg, ftattn_ctx** out) {
   if (cfg->block_n != 0 && cfg->block_n != BN) return fail(nullptr, FTATTN_EUNSUPPORTED, "block_n must be 64");
   if (cfg->block_m != 0 && cfg->block_m != BM) return fail(nullptr, FTATTN_EUNSUPPORTED, "block_m must be 256");
   if (cfg->causal != 0 && cfg->causal != 1) return fail(nullptr, FTATTN_EINVAL, "causal must be 0 or 1");
+  if (cfg->rowsum_fold != 0 && cfg->rowsum_fold != 1) return fail(nullptr, FTATTN_EINVAL, "rowsum_fold must be 0 or 1");
 
   ftattn_ctx* c = new (std::nothrow) ftattn_ctx();
   if (!c) return fail(nullptr, FTATTN_ENOMEM, "out of host memory");
@@ -228,10 +229,10 @@ extern "C" int ftattn_forward(ftattn_ctx* c, const void* q, const void* k, const
   const int bf = e.in_dtype == FTATTN_BF16 ? 1 : 0;
   if (D == 128) {
     ftattn_encode_k<128><<<eg, 128, 0, st>>>(k, bf, c->kc, N, c->Tj, ft ? 1 : 0);
-    ftattn_encode_v<128><<<eg, 256, 0, st>>>(v, bf, c->vt, N, c->Tj, ft ? 1 : 0);
+    ftattn_encode_v<128><<<eg, 256, 0, st>>>(v, bf, c->vt, N, c->Tj, ft ? 1 + e.rowsum_fold : 0);
   } else {
     ftattn_encode_k<64><<<eg, 64, 0, st>>>(k, bf, c->kc, N, c->Tj, ft ? 1 : 0);
-    ftattn_encode_v<64><<<eg, 256, 0, st>>>(v, bf, c->vt, N, c->Tj, ft ? 1 : 0);
+    ftattn_encode_v<64><<<eg, 256, 0, st>>>(v, bf, c->vt, N, c->Tj, ft ? 1 + e.rowsum_fold : 0);
   }
 
   // ---- the fused pass
@@ -244,6 +245,7 @@ extern "C" int ftattn_forward(ftattn_ctx* c, const void* q, const void* k, const
   a.tau_fast = 0.5f * (1.0f - std::exp(-e.eps1));
   a.tau_o = e.tau_o; a.delta_l = e.delta_l;
   a.correct = e.ft_mode == FTATTN_FT_CORRECT ? 1 : 0;
+  a.rowsum_fold = e.rowsum_fold;
   a.faults = c->d_faults;
   a.fault_off = n_faults > 0 ? c->d_fault_off : nullptr;
   a.events = c->d_events; a.ev_count = c->d_ev_count; a.max_events = e.max_events;

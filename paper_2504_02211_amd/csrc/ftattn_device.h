@@ -53,6 +53,7 @@ struct KArgs {
   float scale_log2;        // sigma * log2(e)
   float eps1, tau_fast, tau_o, delta_l;
   int32_t correct;         // 1: repair, 0: detect only
+  int32_t rowsum_fold;     // 1: the row-sum is an extra fold of checksum class 0 of the value tiles
   const DevFault* faults;  // sorted by (bh, row tile, kv_tile)
   const int32_t* fault_off;  // [BH*Ti + 1] or nullptr
   ftattn_event* events;
@@ -204,6 +205,8 @@ __device__ __forceinline__ int vt_key(int p) {
 template <int D>
 __global__ __launch_bounds__(256) void ftattn_encode_v(const void* __restrict__ v, int bf16, _Float16* __restrict__ vt,
                                                        int N, int Tj, int with_checksums) {
+  // with_checksums == 2: class 0 also folds a column of ones at feature index D (fold D/8), which
+  // makes the first checksum of class 0 carry the row-sum through GEMM II
   constexpr int KCH = D / 8, PITCH = D + 8;
   __shared__ __attribute__((aligned(16))) _Float16 tile[BN * PITCH];
   __shared__ __attribute__((aligned(16))) _Float16 cks[CKR * BN];
@@ -234,6 +237,7 @@ __global__ __launch_bounds__(256) void ftattn_encode_v(const void* __restrict__ 
       c1 += x;
       c2 += (float)(l + 1) * x;
     }
+    if (with_checksums == 2 && cls == 0 && j * BN + kl < N) { c1 += 1.0f; c2 += (float)(D / 8 + 1); }
     const _Float16 h1 = (_Float16)c1, h2 = (_Float16)c2;
     const int p = vt_pos(kl);
     cks[cls * BN + p] = h1;

@@ -552,7 +552,56 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
   {
     const bool real = row < N;
     float l = sum32(l_part);
-    if (FT) {
+    const bool lfold = FT && a.rowsum_fold != 0;
+    if (FT && lfold) {
+      // The row-sum as fold NFOLD_V of checksum class 0 (held by the lane half hi == 0, register
+      // r == 0): the row-sum the checksum implies against the accumulated one, in units of the
+      // row-sum; on a mismatch the location rule over the NFOLD_V + 1 folds decides whether the
+      // row-sum is the wrong element, and if so it is replaced by the implied one.
+      float sumx = 0.f;
+#pragma unroll
+      for (int fb = 0; fb < NFB; ++fb)
+#pragma unroll
+        for (int gg = 0; gg < 4; ++gg) sumx += o[fb][4 * gg];
+      const float chk1 = oc[0] + oc[4];
+      const float lc = chk1 - sumx;
+      const float rr = (lc - l) / lc;
+      const bool detl = real && hi == 0 && (!(__builtin_fabsf(rr) <= a.tau_o) || !finitef(rr));
+      if (!detl && real && hi == 0) rmax_u = fmax2(rmax_u, __builtin_fabsf(rr));
+      if (wave_any(detl)) {
+        if (detl) {
+          const float chk2 = oc[8] + oc[12];
+          float sum2 = (float)(NFOLD_V + 1) * l;
+          float big = finitef(l) ? __builtin_fabsf(l) : __builtin_inff();
+          int l_big = NFOLD_V;
+#pragma unroll
+          for (int fb = 0; fb < NFB; ++fb)
+#pragma unroll
+            for (int gg = 0; gg < 4; ++gg) {
+              const float ov = o[fb][4 * gg];
+              sum2 += (float)(4 * fb + gg + 1) * ov;
+              const float mag = finitef(ov) ? __builtin_fabsf(ov) : __builtin_inff();
+              if (mag > big) { big = mag; l_big = 4 * fb + gg; } else if (mag == big) { l_big = -1; }
+            }
+          const float ratio = (chk2 - sum2) / (lc - l);
+          int lstar = -1;
+          if (finitef(ratio)) {
+            const float c = __builtin_rintf(ratio) - 1.0f;
+            if (c >= 0.f && c < (float)(NFOLD_V + 1)) lstar = (int)c;
+          } else {
+            lstar = l_big;
+          }
+          if (lstar == NFOLD_V) {
+            log_event(a, bh, FTATTN_CHECK_L, -1, row, 0, rr, a.correct ? 1 : 0);
+            if (a.correct) l = lc;
+          }
+        }
+      }
+      // the other half of the row takes the row-sum of the half that checked it
+      const float lp = xchg32(l, hi);
+      if (hi == 1) l = lp;
+    }
+    if (FT && !lfold) {
       float Ub = CAUSAL ? (float)(row + 1 < N ? row + 1 : N) : (float)N;
       float lo = l_low;
       bool detl = real && !(lo * (1.f - a.delta_l) <= l && l <= Ub * (1.f + a.delta_l));
@@ -576,6 +625,7 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
         for (int fb = 0; fb < NFB; ++fb)
 #pragma unroll
           for (int gg = 0; gg < 4; ++gg) sum1 += o[fb][4 * gg + r];
+        if (r == 0 && lfold && hi == 0) sum1 += l * inv;      // the normalised extra fold of class 0
         R[r] = (oc[r] + oc[4 + r]) - sum1;
         bool d = real && !(__builtin_fabsf(R[r]) <= a.tau_o);
         bad |= d;
@@ -597,19 +647,27 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
                 float mag = finitef(ov) ? __builtin_fabsf(ov) : __builtin_inff();
                 if (mag > big) { big = mag; l_big = 4 * fb + gg; } else if (mag == big) { l_big = -1; }
               }
+            const bool xfold = r == 0 && lfold && hi == 0;      // class 0 has the row-sum as fold NFOLD_V
+            const float xv = l * inv;
+            if (xfold) {
+              sum2 += (float)(NFOLD_V + 1) * xv;
+              float mag = finitef(xv) ? __builtin_fabsf(xv) : __builtin_inff();
+              if (mag > big) { big = mag; l_big = NFOLD_V; } else if (mag == big) { l_big = -1; }
+            }
             float ratio = (chk2 - sum2) / R[r];
             int lstar = -1;
             if (finitef(ratio)) {
               float c = __builtin_rintf(ratio) - 1.0f;
-              if (c >= 0.f && c < (float)NFOLD_V) lstar = (int)c;
+              if (c >= 0.f && c < (float)(xfold ? NFOLD_V + 1 : NFOLD_V)) lstar = (int)c;
             } else {
               lstar = l_big;
             }
+            if (xfold && lstar == NFOLD_V) continue;             // the row-sum itself: reported above
             int col = lstar >= 0 ? 8 * lstar + 4 * hi + r : -1;
             bool fix = a.correct && lstar >= 0;
             log_event(a, bh, FTATTN_CHECK_O, -1, row, col, R[r], fix ? 1 : 0);
             if (fix) {
-              float rest = 0.f;
+              float rest = xfold ? xv : 0.f;
 #pragma unroll
               for (int fb = 0; fb < NFB; ++fb)
 #pragma unroll
