@@ -117,14 +117,16 @@ def bench_linear(args):
     import torch
     from paper_2504_02211_amd import ftgemm, synth
     m, n, k = 16384, 16384, 4096
-    xb, wb = synth.gen_linear(m, n, k, synth.LINEAR_SEED_BASE + 5)
-    dev = lambda b: torch.from_numpy(b.view(np.int16)).cuda().view(torch.float16)
+    dt = synth.BF16 if args.linear_dtype == "bf16" else synth.F16
+    tdt = torch.bfloat16 if dt == synth.BF16 else torch.float16
+    xb, wb = synth.gen_linear(m, n, k, synth.LINEAR_SEED_BASE + 5, dtype=dt)
+    dev = lambda b: torch.from_numpy(b.view(np.int16)).cuda().view(tdt)
     x, w = dev(xb), dev(wb)
-    y = torch.empty((m, n), dtype=torch.float16, device="cuda")
+    y = torch.empty((m, n), dtype=tdt, device="cuda")
     flops = 2.0 * m * n * k
     res = {}
     for name, mode in (("ft", ftgemm.FT_CORRECT), ("off", ftgemm.FT_OFF)):
-        ctx = ftgemm.FtGemm(m, n, k, out_dtype=ftgemm.F16, ft_mode=mode)
+        ctx = ftgemm.FtGemm(m, n, k, out_dtype=dt, ft_mode=mode, in_dtype=dt)
         stream = torch.cuda.Stream()
         sp = stream.cuda_stream
         ctx.set_timing(True)
@@ -155,8 +157,8 @@ def bench_linear(args):
     out = {"metric": "FT-linear (strided ABFT GEMM) TFLOP/s at 1 GPU, % overhead vs unprotected, % MFMA peak",
            "value": round(tf, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
            "ms_per_step": round(ft["ms_step"], 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-           "dtype": "f16", "data": "synthetic",
-           "config": {"workload": f"feed-forward up-projection: {m} tokens, {k} -> {n} features, fp16 in, fp16 out, "
+           "dtype": args.linear_dtype.replace("fp", "f"), "data": "synthetic",
+           "config": {"workload": f"feed-forward up-projection: {m} tokens, {k} -> {n} features, {args.linear_dtype} in, {args.linear_dtype} out, "
                                   f"fault-free", "block_n": 256, "stride": 8},
            "unprotected_tflops": round(flops / un["ms_step"] / 1e9, 2),
            "unprotected_ms_per_step": round(un["ms_step"], 4),
@@ -176,18 +178,18 @@ def bench_linear(args):
     if not args.no_cpu_baseline:
         from oracle import ftgemm_oracle as orc
         rows = 256
-        X, W = synth.bits_to_f64(xb[:rows], synth.F16), synth.bits_to_f64(wb, synth.F16)
+        X, W = synth.bits_to_f64(xb[:rows], dt), synth.bits_to_f64(wb, dt)
         try:
             from threadpoolctl import threadpool_info
             cores = max([p_.get("num_threads", 1) for p_ in threadpool_info()] + [1])
         except Exception:
             cores = os.cpu_count() or 1
         t0 = time.perf_counter()
-        orc.ftgemm(X, W, orc.Params())
-        dt = time.perf_counter() - t0
-        out["cpu_baseline"] = {"value": round(2.0 * rows * n * k / dt / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores),
+        orc.ftgemm(X, W, orc.Params(bf16=dt == synth.BF16))
+        secs = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(2.0 * rows * n * k / secs / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores),
                                "kind": "oracle", "sample": f"the first {rows} token rows of the same workload through the "
-                               f"fp64 oracle (product, checksum products, verification), {dt:.1f} s; useful flops only"}
+                               f"fp64 oracle (product, checksum products, verification), {secs:.1f} s; useful flops only"}
     print(json.dumps(out))
     return 0
 
@@ -205,6 +207,7 @@ def main():
                     help="attention: protect the row-sum as an extra fold of checksum class 0 (exact check) instead of the range restriction")
     ap.add_argument("--linear", action="store_true",
                     help="time the protected feed-forward GEMM instead of attention (its own JSON line)")
+    ap.add_argument("--linear-dtype", choices=("fp16", "bf16"), default="fp16")
     ap.add_argument("--pmc-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (calibration of HBM byte counters under rocprofv3 --pmc)")
     args = ap.parse_args()

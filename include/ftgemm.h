@@ -7,11 +7,11 @@
  * (14), and "Strided ABFT with Tensor Checksum", eq. (15), (16); Figure 1 shows the feed-forward
  * module under that protection).  This library computes
  *
- *     Y = X W^T,    X: [m, k] fp16 (tokens),  W: [n, k] fp16 (weights),  Y: [m, n] fp32 or fp16,
+ *     Y = X W^T,    X: [m, k] (tokens),  W: [n, k] (weights), fp16 or bf16,  Y: [m, n] fp32 or the input type,
  *
  * in one kernel that carries, for every block of 256 output features, the two stride-8 tensor
  * checksums of the weight rows (weights 1 and l+1) through the contraction as 32 extra MFMA
- * rows (each checksum as an fp16 high word and an fp16 low word), and after the last
+ * rows (each checksum as a high word and a low word of the input type), and after the last
  * accumulation step compares, per token and checksum class, the fold of the 32 results with the
  * first checksum product.  A mismatch is located with the second checksum (fold = residual
  * ratio - 1) and the element is restored from the first.
@@ -37,7 +37,7 @@ extern "C" {
 
 typedef struct ftgemm_ctx ftgemm_ctx; /* opaque, library-owned */
 
-enum { FTGEMM_F16 = 0, FTGEMM_F32 = 2 };
+enum { FTGEMM_F16 = 0, FTGEMM_BF16 = 1, FTGEMM_F32 = 2 };
 enum { FTGEMM_OK = 0, FTGEMM_EINVAL = -1, FTGEMM_EUNSUPPORTED = -2, FTGEMM_EHIP = -3, FTGEMM_ENOMEM = -4,
        FTGEMM_ESTATE = -5 };
 enum { FTGEMM_FT_OFF = 0, FTGEMM_FT_CORRECT = 1, FTGEMM_FT_DETECT = 2 };
@@ -45,8 +45,9 @@ enum { FTGEMM_FT_OFF = 0, FTGEMM_FT_CORRECT = 1, FTGEMM_FT_DETECT = 2 };
 typedef struct {
   uint32_t struct_size;  /* sizeof(ftgemm_config), checked */
   int32_t m, n, k;       /* m, n >= 1 (any value); k >= 64 and a multiple of 64 */
-  int32_t in_dtype;      /* FTGEMM_F16 */
-  int32_t out_dtype;     /* FTGEMM_F32 | FTGEMM_F16 */
+  int32_t in_dtype;      /* FTGEMM_F16 | FTGEMM_BF16: type of x and w; the contraction runs on the MFMA of
+                            that type with fp32 accumulation */
+  int32_t out_dtype;     /* FTGEMM_F32, or the input type */
   int32_t ft_mode;       /* OFF: same kernel, checks and checksum rows compiled out;
                             CORRECT: detect, locate, restore; DETECT: detect and locate only */
   int32_t stride;        /* checksum stride s of eq. (13); 0 or 8 */

@@ -15,7 +15,7 @@ using namespace ftgemm;
 struct ftgemm_ctx {
   ftgemm_config cfg;          // effective configuration
   int Tm = 0, Tn = 0;
-  _Float16* wc = nullptr;     // [Tn][32][k] checksum rows of the weights
+  uint16_t* wc = nullptr;     // [Tn][32][k] checksum rows of the weights (input type)
   const void* encoded_w = nullptr;
   GFault* d_faults = nullptr;
   ftgemm_event* d_events = nullptr;
@@ -56,9 +56,12 @@ static void grelease(ftgemm_ctx* c) {
 
 typedef void (*gemm_fn)(const GArgs);
 
-static gemm_fn select_gemm(bool ft, bool inject) {
-  if (ft) return inject ? ftgemm_main<true, true> : ftgemm_main<true, false>;
-  return inject ? ftgemm_main<false, true> : ftgemm_main<false, false>;
+template <bool BF> static gemm_fn select_gemm_t(bool ft, bool inject) {
+  if (ft) return inject ? ftgemm_main<true, true, BF> : ftgemm_main<true, false, BF>;
+  return inject ? ftgemm_main<false, true, BF> : ftgemm_main<false, false, BF>;
+}
+static gemm_fn select_gemm(bool ft, bool inject, bool bf) {
+  return bf ? select_gemm_t<true>(ft, inject) : select_gemm_t<false>(ft, inject);
 }
 static size_t gemm_lds(bool ft) { return ft ? GStage<true>::LDS_TOTAL : GStage<false>::LDS_TOTAL; }
 
@@ -68,8 +71,8 @@ extern "C" int ftgemm_create(const ftgemm_config* cfg, ftgemm_ctx** out) {
   if (cfg->struct_size != sizeof(ftgemm_config)) return gfail(nullptr, FTGEMM_EINVAL, "struct_size mismatch");
   if (cfg->m < 1 || cfg->n < 1) return gfail(nullptr, FTGEMM_EINVAL, "m and n must be >= 1");
   if (cfg->k < 64 || cfg->k % 64 != 0) return gfail(nullptr, FTGEMM_EUNSUPPORTED, "k must be a positive multiple of 64");
-  if (cfg->in_dtype != FTGEMM_F16) return gfail(nullptr, FTGEMM_EUNSUPPORTED, "in_dtype must be F16");
-  if (cfg->out_dtype != FTGEMM_F32 && cfg->out_dtype != FTGEMM_F16) return gfail(nullptr, FTGEMM_EINVAL, "out_dtype must be F32 or F16");
+  if (cfg->in_dtype != FTGEMM_F16 && cfg->in_dtype != FTGEMM_BF16) return gfail(nullptr, FTGEMM_EINVAL, "in_dtype must be F16 or BF16");
+  if (cfg->out_dtype != FTGEMM_F32 && cfg->out_dtype != cfg->in_dtype) return gfail(nullptr, FTGEMM_EINVAL, "out_dtype must be F32 or the input type");
   if (cfg->ft_mode < 0 || cfg->ft_mode > 2) return gfail(nullptr, FTGEMM_EINVAL, "ft_mode out of range");
   if (cfg->stride != 0 && cfg->stride != 8) return gfail(nullptr, FTGEMM_EUNSUPPORTED, "stride must be 8");
   if (cfg->block_n != 0 && cfg->block_n != GBN) return gfail(nullptr, FTGEMM_EUNSUPPORTED, "block_n must be 256");
@@ -113,8 +116,8 @@ extern "C" int ftgemm_create(const ftgemm_config* cfg, ftgemm_ctx** out) {
   GCREATE_TRY(hipMemset(c->wc, 0, n_wc * 2));
   GCREATE_TRY(hipMemset(c->d_ev_count, 0, sizeof(int32_t)));
   GCREATE_TRY(hipMemset(c->d_resmax, 0, sizeof(uint32_t)));
-  for (int v = 0; v < 4; ++v)
-    GCREATE_TRY(hipFuncSetAttribute((const void*)select_gemm((v & 1) != 0, (v & 2) != 0),
+  for (int v = 0; v < 8; ++v)
+    GCREATE_TRY(hipFuncSetAttribute((const void*)select_gemm((v & 1) != 0, (v & 2) != 0, (v & 4) != 0),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds((v & 1) != 0)));
   GCREATE_TRY(hipDeviceSynchronize());
 #undef GCREATE_TRY
@@ -135,7 +138,8 @@ extern "C" int ftgemm_encode_weights(ftgemm_ctx* c, const void* w, void* hip_str
   GHIP_TRY(c, hipSetDevice(e.device));
   hipStream_t st = (hipStream_t)hip_stream;
   dim3 grid(c->Tn, (e.k / 8 + 31) / 32);
-  ftgemm_encode_w<<<grid, 256, 0, st>>>(reinterpret_cast<const _Float16*>(w), c->wc, e.n, e.k);
+  if (e.in_dtype == FTGEMM_BF16) ftgemm_encode_w<true><<<grid, 256, 0, st>>>(reinterpret_cast<const uint16_t*>(w), c->wc, e.n, e.k);
+  else ftgemm_encode_w<false><<<grid, 256, 0, st>>>(reinterpret_cast<const uint16_t*>(w), c->wc, e.n, e.k);
   GHIP_TRY(c, hipGetLastError());
   c->encoded_w = w;
   return FTGEMM_OK;
@@ -169,8 +173,8 @@ extern "C" int ftgemm_forward(ftgemm_ctx* c, const void* x, const void* w, void*
   ftgemm_reset<<<1, 64, 0, st>>>(c->d_ev_count, c->d_resmax);
 
   GArgs a;
-  a.x = reinterpret_cast<const _Float16*>(x);
-  a.w = reinterpret_cast<const _Float16*>(w);
+  a.x = reinterpret_cast<const uint16_t*>(x);
+  a.w = reinterpret_cast<const uint16_t*>(w);
   a.wc = c->wc;
   a.y = y; a.out_dtype = e.out_dtype;
   a.M = e.m; a.N = e.n; a.K = e.k; a.Tm = c->Tm; a.Tn = c->Tn;
@@ -179,7 +183,7 @@ extern "C" int ftgemm_forward(ftgemm_ctx* c, const void* x, const void* w, void*
   a.faults = c->d_faults; a.n_faults = n_faults;
   a.events = c->d_events; a.ev_count = c->d_ev_count; a.max_events = e.max_events;
   a.resmax = c->d_resmax;
-  gemm_fn f = select_gemm(ft, n_faults > 0);
+  gemm_fn f = select_gemm(ft, n_faults > 0, e.in_dtype == FTGEMM_BF16);
   if (c->timing) GHIP_TRY(c, hipEventRecord(c->ev[0], st));
   hipLaunchKernelGGL(f, dim3(c->Tm * c->Tn), dim3(GWAVES * 64), gemm_lds(ft), st, a);
   GHIP_TRY(c, hipGetLastError());

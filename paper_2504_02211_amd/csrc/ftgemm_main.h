@@ -1,11 +1,11 @@
 // Fault-tolerant linear layer Y = X W^T for gfx950 / CDNA4: the strided ABFT of Section 3.3 of
 // the paper (tensor checksums of eq. (13), (14); checksum products of eq. (15), (16); location
-// and repair as stated after eq. (16)) on a plain fp16 GEMM with fp32 accumulation.
+// and repair as stated after eq. (16)) on a plain fp16 or bf16 GEMM with fp32 accumulation.
 //
 // Execution shape.  One workgroup computes a 256-token x 256-feature tile of Y; the 256 features
 // are exactly one checksum block.  Eight waves of 64 lanes; wave w owns tokens 32w .. 32w+31 and
 // ALL 256 features of the tile, as eight 32x32 accumulator blocks of Y^T = W X^T (32x32x16 fp16
-// MFMA: the weight rows are the A operand, the token rows the B operand) plus one block for the
+// or bf16 MFMA: the weight rows are the A operand, the token rows the B operand) plus one block for the
 // 32 checksum rows.  A lane then holds one token (column lane%32) and, per block, the features
 // 8*g + 4*(lane/32) + r: feature index mod 8 is 4*(lane/32)+r, so all 32 folds of the four
 // checksum classes a lane sees are in the lane's own registers and verification, location and
@@ -42,11 +42,26 @@ constexpr int ROWB = GBK * 2; // bytes per tile row in LDS
 
 struct GFault { int32_t row, col, bit; };
 
+typedef __bf16 bf8 __attribute__((ext_vector_type(8)));
+
+// 16-bit storage helpers (fp16 or bf16 bit patterns)
+template <bool BF> __device__ __forceinline__ float to_f32(uint16_t u) {
+  if (BF) return as_f((uint32_t)u << 16);
+  return (float)__builtin_bit_cast(_Float16, u);
+}
+// round-to-nearest-even to the storage type (Inf / NaN pass through)
+template <bool BF> __device__ __forceinline__ uint16_t from_f32(float x) {
+  if (!BF) return __builtin_bit_cast(uint16_t, (_Float16)x);
+  const uint32_t u = as_u(x);
+  if ((u & 0x7F800000u) == 0x7F800000u) return (uint16_t)(u >> 16);
+  return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+
 struct GArgs {
-  const _Float16* x;       // [M][K]
-  const _Float16* w;       // [N][K]
-  const _Float16* wc;      // [Tn][GCK][K] checksum rows of W
-  void* y;                 // [M][N] fp32 or fp16
+  const uint16_t* x;       // [M][K] fp16 or bf16 patterns
+  const uint16_t* w;       // [N][K]
+  const uint16_t* wc;      // [Tn][GCK][K] checksum rows of W, same type
+  void* y;                 // [M][N] fp32, or the input type
   int32_t out_dtype;
   int32_t M, N, K, Tm, Tn;
   float tau_rel, tau_abs;
@@ -73,10 +88,12 @@ template <bool FT> struct GStage {
 
 // Tensor checksums of the weight rows of every 256-feature block (eq. (13), (14)): thread =
 // (class c, 16-byte chunk of K); it folds the 32 rows c, c+8, ... of its block in fp32 and
-// stores each of the two sums as an fp16 high word and an fp16 low word.  Rows beyond N count
-// as zero.
-static __global__ __launch_bounds__(256) void ftgemm_encode_w(const _Float16* __restrict__ w, _Float16* __restrict__ wc,
+// stores each of the two sums as a high word and a low word of the input type (high = the sum
+// rounded, low = the remainder rounded).  Rows beyond N count as zero.
+template <bool BF>
+__global__ __launch_bounds__(256) void ftgemm_encode_w(const uint16_t* __restrict__ w, uint16_t* __restrict__ wc,
                                                        int N, int K) {
+  typedef uint16_t u16x8 __attribute__((ext_vector_type(8)));
   const int tn = blockIdx.x, tid = threadIdx.x;
   const int cls = tid >> 5, ch = blockIdx.y * 32 + (tid & 31);
   if (ch * 8 >= K) return;
@@ -86,25 +103,25 @@ static __global__ __launch_bounds__(256) void ftgemm_encode_w(const _Float16* __
   for (int l = 0; l < GFOLD; ++l) {
     const int n = tn * GBN + cls + 8 * l;
     if (n >= N) break;
-    const half8 h = *reinterpret_cast<const half8*>(w + (size_t)n * K + ch * 8);
+    const u16x8 h = *reinterpret_cast<const u16x8*>(w + (size_t)n * K + ch * 8);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const float v = (float)h[e];
+      const float v = to_f32<BF>(h[e]);
       c1[e] += v;
       c2[e] += (float)(l + 1) * v;
     }
   }
-  half8 w0, w1, w2, w3;
+  u16x8 w0, w1, w2, w3;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    w0[e] = (_Float16)c1[e]; w1[e] = (_Float16)(c1[e] - (float)w0[e]);
-    w2[e] = (_Float16)c2[e]; w3[e] = (_Float16)(c2[e] - (float)w2[e]);
+    w0[e] = from_f32<BF>(c1[e]); w1[e] = from_f32<BF>(c1[e] - to_f32<BF>(w0[e]));
+    w2[e] = from_f32<BF>(c2[e]); w3[e] = from_f32<BF>(c2[e] - to_f32<BF>(w2[e]));
   }
-  _Float16* out = wc + (size_t)tn * GCK * K + ch * 8;
-  *reinterpret_cast<half8*>(out + (size_t)(cls) * K) = w0;
-  *reinterpret_cast<half8*>(out + (size_t)(8 + cls) * K) = w1;
-  *reinterpret_cast<half8*>(out + (size_t)(16 + cls) * K) = w2;
-  *reinterpret_cast<half8*>(out + (size_t)(24 + cls) * K) = w3;
+  uint16_t* out = wc + (size_t)tn * GCK * K + ch * 8;
+  *reinterpret_cast<u16x8*>(out + (size_t)(cls) * K) = w0;
+  *reinterpret_cast<u16x8*>(out + (size_t)(8 + cls) * K) = w1;
+  *reinterpret_cast<u16x8*>(out + (size_t)(16 + cls) * K) = w2;
+  *reinterpret_cast<u16x8*>(out + (size_t)(24 + cls) * K) = w3;
 }
 
 static __global__ void ftgemm_reset(int32_t* ev_count, uint32_t* resmax) {
@@ -120,7 +137,7 @@ __device__ __forceinline__ void log_gemm_event(const GArgs& a, int row, int col,
   }
 }
 
-template <bool FT, bool INJ>
+template <bool FT, bool INJ, bool BF>
 __global__ __launch_bounds__(GWAVES * 64) void ftgemm_main(const GArgs a) {
   using S = GStage<FT>;
   constexpr int NA = FT ? 9 : 8;          // A operands (32-row blocks of W, + the checksum block) per k-step
@@ -172,9 +189,9 @@ __global__ __launch_bounds__(GWAVES * 64) void ftgemm_main(const GArgs a) {
     if (r > rows_left - 1) r = rows_left - 1;
     off[i] = ((uint32_t)r * (uint32_t)K + (uint32_t)c * 8u) * 2u;
   }
-  const _Float16* xb = a.x + (size_t)m0 * K;
-  const _Float16* wb = a.w + (size_t)n0 * K;
-  const _Float16* cb = FT ? a.wc + (size_t)tn * GCK * K : a.w;
+  const uint16_t* xb = a.x + (size_t)m0 * K;
+  const uint16_t* wb = a.w + (size_t)n0 * K;
+  const uint16_t* cb = FT ? a.wc + (size_t)tn * GCK * K : a.w;
   const uint32_t dump = smem_base + 2u * S::BYTES;
   auto issue_piece = [&](int i, int kb, int st, bool real_piece) __attribute__((always_inline)) {
     const bool ok = real_piece && (i < 8 || wave < 4);
@@ -223,8 +240,9 @@ __global__ __launch_bounds__(GWAVES * 64) void ftgemm_main(const GArgs a) {
       if (k < S::NLOAD) issue_piece(k, kb + 1, st ^ 1, more);
       const half8 av = buf[k % RING];
       const int ks = k / NA, y = k % NA;
-      if (y < 8) acc[y] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, xf[ks], acc[y], 0, 0, 0);
-      else sc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, xf[ks], sc, 0, 0, 0);
+      float16v& dst = y < 8 ? acc[y] : sc;
+      if (BF) dst = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf8, av), __builtin_bit_cast(bf8, xf[ks]), dst, 0, 0, 0);
+      else dst = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, xf[ks], dst, 0, 0, 0);
     }
   }
 
@@ -339,8 +357,8 @@ __global__ __launch_bounds__(GWAVES * 64) void ftgemm_main(const GArgs a) {
           if (a.out_dtype == FTGEMM_F32) {
             *reinterpret_cast<float4*>(reinterpret_cast<float*>(a.y) + base + col) = make_float4(x0, x1, x2, x3);
           } else {
-            _Float16 hv[4] = {(_Float16)x0, (_Float16)x1, (_Float16)x2, (_Float16)x3};
-            *reinterpret_cast<uint2*>(reinterpret_cast<_Float16*>(a.y) + base + col) = *reinterpret_cast<uint2*>(hv);
+            uint16_t hv[4] = {from_f32<BF>(x0), from_f32<BF>(x1), from_f32<BF>(x2), from_f32<BF>(x3)};
+            *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(a.y) + base + col) = *reinterpret_cast<uint2*>(hv);
           }
         } else {
           const float xs[4] = {x0, x1, x2, x3};
@@ -348,7 +366,7 @@ __global__ __launch_bounds__(GWAVES * 64) void ftgemm_main(const GArgs a) {
           for (int e = 0; e < 4; ++e)
             if (col + e < N) {
               if (a.out_dtype == FTGEMM_F32) reinterpret_cast<float*>(a.y)[base + col + e] = xs[e];
-              else reinterpret_cast<_Float16*>(a.y)[base + col + e] = (_Float16)xs[e];
+              else reinterpret_cast<uint16_t*>(a.y)[base + col + e] = from_f32<BF>(xs[e]);
             }
         }
       }

@@ -13,7 +13,7 @@ import numpy as np
 
 from . import ftattn as _base
 
-F16, F32 = 0, 2
+F16, BF16, F32 = 0, 1, 2
 FT_OFF, FT_CORRECT, FT_DETECT = 0, 1, 2
 OK, EINVAL, EUNSUPPORTED, EHIP, ENOMEM, ESTATE = 0, -1, -2, -3, -4, -5
 
@@ -98,9 +98,9 @@ class FtGemm:
     """One context of the C library: Y = X W^T for one (m, n, k) on one device."""
 
     def __init__(self, m: int, n: int, k: int, out_dtype: int = F32, ft_mode: int = FT_CORRECT, tau_rel: float = 0.0,
-                 tau_abs: float = -1.0, max_events: int = 0, device: int = 0):
+                 tau_abs: float = -1.0, max_events: int = 0, device: int = 0, in_dtype: int = F16):
         self.lib = load_library()
-        cfg = Config(C.sizeof(Config), m, n, k, F16, out_dtype, ft_mode, 8, 0, tau_rel, tau_abs, max_events, device)
+        cfg = Config(C.sizeof(Config), m, n, k, in_dtype, out_dtype, ft_mode, 8, 0, tau_rel, tau_abs, max_events, device)
         self.handle = C.c_void_p()
         rc = self.lib.ftgemm_create(C.byref(cfg), C.byref(self.handle))
         if rc != OK:

@@ -227,9 +227,9 @@ def faults_to_array(faults: List[Tuple[int, ...]]) -> np.ndarray:
 LINEAR_SEED_BASE = 0xF7A7A000
 
 
-def gen_linear(m: int, n: int, k: int, seed: int, x_scale: float = 1.0):
+def gen_linear(m: int, n: int, k: int, seed: int, x_scale: float = 1.0, dtype: int = F16):
     """Activations X [m, k] ~ N(0, x_scale^2) and weights W [n, k] ~ N(0, 1/k) (so that the
-    outputs are of order x_scale), rounded to fp16; returns two uint16 arrays.  Rows are drawn
+    outputs are of order x_scale), rounded to ``dtype``; returns two uint16 arrays.  Rows are drawn
     from per-row-block Philox streams so that a slice can be regenerated on its own."""
     x = np.zeros((m, k), np.uint16)
     w = np.zeros((n, k), np.uint16)
@@ -237,7 +237,7 @@ def gen_linear(m: int, n: int, k: int, seed: int, x_scale: float = 1.0):
         for r0 in range(0, rows, 1024):
             rng = np.random.Generator(np.random.Philox(key=[seed & 0xFFFFFFFFFFFFFFFF, (which << 40) | r0]))
             nr = min(1024, rows - r0)
-            arr[r0:r0 + nr] = to_bits(rng.standard_normal((nr, k)) * sc, F16)
+            arr[r0:r0 + nr] = to_bits(rng.standard_normal((nr, k)) * sc, dtype)
     return x, w
 
 

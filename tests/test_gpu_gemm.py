@@ -19,16 +19,19 @@ pytestmark = pytest.mark.gpu
 TOL32 = 1e-4
 
 
-def dev16(bits):
-    return torch.from_numpy(bits.view(np.int16)).to("cuda").view(torch.float16)
+TORCH_T = {ftgemm.F16: torch.float16, ftgemm.BF16: torch.bfloat16, ftgemm.F32: torch.float32}
 
 
-def run(xb, wb, ft_mode, out_dtype=ftgemm.F32, faults=None, encode=True, **kw):
+def dev16(bits, dtype=synth.F16):
+    return torch.from_numpy(bits.view(np.int16)).to("cuda").view(TORCH_T[dtype])
+
+
+def run(xb, wb, ft_mode, out_dtype=ftgemm.F32, faults=None, encode=True, dtype=synth.F16, **kw):
     m, k = xb.shape
     n = wb.shape[0]
-    ctx = ftgemm.FtGemm(m, n, k, out_dtype=out_dtype, ft_mode=ft_mode, **kw)
-    x, w = dev16(xb), dev16(wb)
-    y = torch.full((m, n), float("nan"), dtype=torch.float32 if out_dtype == ftgemm.F32 else torch.float16, device="cuda")
+    ctx = ftgemm.FtGemm(m, n, k, out_dtype=out_dtype, ft_mode=ft_mode, in_dtype=dtype, **kw)
+    x, w = dev16(xb, dtype), dev16(wb, dtype)
+    y = torch.full((m, n), float("nan"), dtype=TORCH_T[out_dtype], device="cuda")
     st = torch.cuda.current_stream().cuda_stream
     if encode:
         ctx.encode_weights(w, st)
@@ -39,8 +42,8 @@ def run(xb, wb, ft_mode, out_dtype=ftgemm.F32, faults=None, encode=True, **kw):
     return y.double().cpu().numpy(), rep, cfg
 
 
-def f64(bits):
-    return synth.bits_to_f64(bits, synth.F16)
+def f64(bits, dtype=synth.F16):
+    return synth.bits_to_f64(bits, dtype)
 
 
 SHAPES = [(256, 256, 64), (300, 520, 128), (515, 777, 192), (1024, 1024, 512), (33, 9, 64), (1, 1, 64)]
@@ -48,23 +51,27 @@ SHAPES = [(256, 256, 64), (300, 520, 128), (515, 777, 192), (1024, 1024, 512), (
 
 @pytest.mark.parametrize("m,n,k", SHAPES)
 @pytest.mark.parametrize("ft_mode", [ftgemm.FT_OFF, ftgemm.FT_CORRECT])
-def test_fault_free_output_matches_the_definition(m, n, k, ft_mode):
-    print(f"[gemm clean] m={m} n={n} k={k} ft={ft_mode}", flush=True)
-    xb, wb = synth.gen_linear(m, n, k, synth.LINEAR_SEED_BASE + m)
-    want = orc.linear_clean(f64(xb), f64(wb))
-    got, rep, _ = run(xb, wb, ft_mode)
+@pytest.mark.parametrize("dtype", [synth.F16, synth.BF16])
+def test_fault_free_output_matches_the_definition(m, n, k, ft_mode, dtype):
+    print(f"[gemm clean] m={m} n={n} k={k} ft={ft_mode} dtype={dtype}", flush=True)
+    xb, wb = synth.gen_linear(m, n, k, synth.LINEAR_SEED_BASE + m, dtype=dtype)
+    want = orc.linear_clean(f64(xb, dtype), f64(wb, dtype))
+    got, rep, _ = run(xb, wb, ft_mode, dtype=dtype)
     assert np.isfinite(got).all()
     assert np.abs(got - want).max() <= TOL32
     assert rep.n_events == 0 and rep.n_events_dropped == 0
     if ft_mode != ftgemm.FT_OFF and n >= 8:
-        assert 0.0 < rep.residual_max < 0.25      # fault-free residuals sit well below the threshold
+        # fault-free residuals sit below the threshold: far below with fp16 checksum words (22
+        # bits), closer with bf16 words (16 bits)
+        assert 0.0 < rep.residual_max < (0.25 if dtype == synth.F16 else 0.7)
 
 
-def test_fp16_output():
-    xb, wb = synth.gen_linear(300, 520, 128, synth.LINEAR_SEED_BASE + 1)
-    want = orc.linear_clean(f64(xb), f64(wb))
-    got, rep, _ = run(xb, wb, ftgemm.FT_CORRECT, out_dtype=ftgemm.F16)
-    assert np.all(np.abs(got - want) <= 2.0 ** -10 * np.maximum(1.0, np.abs(want)))
+@pytest.mark.parametrize("dtype,ulp", [(synth.F16, 2.0 ** -10), (synth.BF16, 2.0 ** -7)])
+def test_16_bit_output(dtype, ulp):
+    xb, wb = synth.gen_linear(300, 520, 128, synth.LINEAR_SEED_BASE + 1, dtype=dtype)
+    want = orc.linear_clean(f64(xb, dtype), f64(wb, dtype))
+    got, rep, _ = run(xb, wb, ftgemm.FT_CORRECT, out_dtype=dtype, dtype=dtype)
+    assert np.all(np.abs(got - want) <= ulp * np.maximum(1.0, np.abs(want)))
     assert rep.n_events == 0
 
 
@@ -88,12 +95,16 @@ def select_faults(X, W, prm, n_faults, seed, bit_lo, bit_hi):
     return np.asarray(accepted, np.int32)
 
 
-@pytest.mark.parametrize("m,n,k,bits", [(512, 768, 256, (20, 30)), (300, 520, 128, (0, 31)), (515, 777, 192, (10, 31))])
-def test_injected_faults_are_detected_located_and_repaired_as_the_oracle_says(m, n, k, bits):
-    print(f"[gemm faults] m={m} n={n} k={k} bits={bits}", flush=True)
-    xb, wb = synth.gen_linear(m, n, k, synth.LINEAR_SEED_BASE + 2)
-    X, W = f64(xb), f64(wb)
-    prm = orc.Params()
+@pytest.mark.parametrize("m,n,k,bits,dtype", [(512, 768, 256, (20, 30), synth.F16), (300, 520, 128, (0, 31), synth.F16),
+                                              (515, 777, 192, (10, 31), synth.F16), (512, 768, 256, (18, 30), synth.BF16),
+                                              (300, 520, 2048, (0, 31), synth.BF16)])
+def test_injected_faults_are_detected_located_and_repaired_as_the_oracle_says(m, n, k, bits, dtype):
+    print(f"[gemm faults] m={m} n={n} k={k} bits={bits} dtype={dtype}", flush=True)
+    xb, wb = synth.gen_linear(m, n, k, synth.LINEAR_SEED_BASE + 2, dtype=dtype)
+    X, W = f64(xb, dtype), f64(wb, dtype)
+    prm = orc.Params(bf16=dtype == synth.BF16)
+    # a value restored from bf16 checksum words carries their 16-bit precision
+    tol_fix = TOL32 if dtype == synth.F16 else 4e-3
     faults = select_faults(X, W, prm, 32, synth.LINEAR_SEED_BASE + 3, *bits)
     clean_rows = np.setdiff1d(np.arange(0, m, 37), faults[:, 0])
     rows = np.concatenate([faults[:, 0], clean_rows])
@@ -101,7 +112,7 @@ def test_injected_faults_are_detected_located_and_repaired_as_the_oracle_says(m,
     for mode, correct in ((ftgemm.FT_CORRECT, True), (ftgemm.FT_DETECT, False)):
         prm.correct = correct
         want, ev, _ = orc.ftgemm(X[rows], W, prm, local)
-        got, rep, cfg = run(xb, wb, mode, faults=faults)
+        got, rep, cfg = run(xb, wb, mode, faults=faults, dtype=dtype)
         assert cfg.tau_rel == np.float32(prm.tau_rel) and cfg.block_n == prm.block_n
         ev_global = sorted((int(rows[r]), c, a) for (r, c, a) in ev)
         assert rep.event_list() == ev_global
@@ -111,14 +122,14 @@ def test_injected_faults_are_detected_located_and_repaired_as_the_oracle_says(m,
         assert np.array_equal(np.isfinite(g), fin)
         # damaged values left in place (detect-only, or flips below the threshold) differ from the
         # oracle's by what the flip does to the last bits of two different roundings of the same sum
-        assert np.all(np.abs(g[fin] - w_[fin]) <= TOL32 * np.maximum(1.0, np.abs(w_[fin])))
+        assert np.all(np.abs(g[fin] - w_[fin]) <= tol_fix * np.maximum(1.0, np.abs(w_[fin])))
         if correct:
             harmful = [e for e in ev_global if e[2] == 1]
             assert len(harmful) == len(ev_global)          # every located fault was repaired
             ref = orc.linear_clean(X[rows], W)
             flagged_rows = {r for (r, _, _) in ev_global}
             sel = np.array([rr in flagged_rows for rr in rows])
-            assert np.abs(g[sel] - ref[sel]).max() <= TOL32
+            assert np.abs(g[sel] - ref[sel]).max() <= tol_fix
 
 
 def test_unprotected_run_shows_the_damage():

@@ -77,8 +77,9 @@ def test_gemm_create_rejects_bad_configs_without_a_device():
     assert create(m=0)[0] == ftgemm.EINVAL
     assert create(k=96)[0] == ftgemm.EUNSUPPORTED
     assert create(k=0)[0] == ftgemm.EUNSUPPORTED
-    assert create(in_dtype=1)[0] == ftgemm.EUNSUPPORTED
-    assert create(out_dtype=1)[0] == ftgemm.EINVAL
+    assert create(in_dtype=2)[0] == ftgemm.EINVAL
+    assert create(out_dtype=1)[0] == ftgemm.EINVAL          # bf16 out for fp16 in
+    assert create(in_dtype=1, out_dtype=0)[0] == ftgemm.EINVAL
     assert create(stride=4)[0] == ftgemm.EUNSUPPORTED
     assert create(ft_mode=3)[0] == ftgemm.EINVAL
     rc, msg = create(block_n=128)

@@ -45,6 +45,33 @@ def test_two_words_hold_the_checksum():
     assert np.array_equal(lo, np.zeros(3))
 
 
+def test_bf16_words():
+    """bf16 keeps 8 significant bits: rounding is to nearest even, two words hold 16 bits."""
+    x = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -7, -3.1415926, 65280.0, 0.0])
+    r = orc.round_bf16(x)
+    assert r.tolist()[:4] == [1.0, 1.0, 1.0 + 2.0 ** -6, 1.0 + 2.0 ** -7] and r[5] == 65280.0 and r[6] == 0.0
+    assert abs(r[4] + 3.1415926) <= 2.0 ** -7
+    rng = np.random.default_rng(33)
+    c = rng.standard_normal((8, 64)) * 11.0
+    hi, lo = orc.two_fp16_words(c, bf16=True)
+    assert np.array_equal(hi, orc.round_bf16(hi)) and np.array_equal(lo, orc.round_bf16(lo))
+    assert np.max(np.abs(hi + lo - c) / np.abs(c)) < 2.0 ** -15
+    assert np.max(np.abs(hi - c) / np.abs(c)) <= 2.0 ** -8
+
+
+def test_bf16_inputs_stay_below_the_threshold_and_faults_are_repaired():
+    rng = np.random.default_rng(34)
+    X = orc.round_bf16(rng.standard_normal((8, 256)))
+    W = orc.round_bf16(rng.standard_normal((512, 256)) / 16)
+    prm = orc.Params(bf16=True)
+    Yref = X @ W.T
+    Y, ev, dg = orc.ftgemm(X, W, prm)
+    assert ev == [] and 0.0 < dg["res_max"] < 0.5
+    Y, ev, _ = orc.ftgemm(X, W, prm, [(5, 300, 24)])
+    assert ev == [(5, 300, 1)]
+    assert np.max(np.abs(Y - Yref)) < 2e-3          # restored from bf16 checksum words: 16 bits
+
+
 def test_checksum_identity_is_exact_on_integers():
     """eq. (15): X check1^T equals the stride-8 fold of Y; with small integers every sum is exact,
     so the residual is exactly zero and nothing is flagged even at a zero threshold."""
