@@ -99,24 +99,20 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
   const _Float16* vt_head = a.vt + (size_t)bh * a.Tj * VT_ELEMS;
   const uint32_t smem_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
 
-  // ---- per-lane source offsets of this wave's load instructions (the same for every tile)
-  uint32_t koff[U::KPW], voff[U::VPW];
-#pragma unroll
-  for (int i = 0; i < U::KPW; ++i) {
-    int ins = wave + NWAVE * i;
-    if (ins >= U::K_INSTR) ins = wave;             // a piece this wave does not have: any valid source will do
-    int L = ins * 64 + lane;
-    int r = L / KCH, c = (L % KCH) ^ swz_k<D>(r);
-    koff[i] = (uint32_t)(r * D + c * 8) * 2u;
+  // ---- per-lane source offsets of this wave's load instructions (the same for every tile).
+  // Instruction wave + 8*i of a tile reads rows 512/chunks-per-row further down than instruction
+  // wave, i.e. 8192 bytes further in either tile, and the swizzle of a row does not change over
+  // that distance: one offset per tile kind is kept, the rest is added to the scalar base.
+  uint32_t koff0, voff0;
+  {
+    const int L = wave * 64 + lane;
+    const int rk = L / KCH, ck = (L % KCH) ^ swz_k<D>(rk);
+    koff0 = (uint32_t)(rk * D + ck * 8) * 2u;
+    const int rv = L / 8, cv = (L % 8) ^ swz_v(rv);
+    voff0 = (uint32_t)(rv * BN + cv * 8) * 2u;
   }
-#pragma unroll
-  for (int i = 0; i < U::VPW; ++i) {
-    int ins = wave + NWAVE * i;
-    if (ins >= U::V_INSTR) ins = wave;
-    int L = ins * 64 + lane;
-    int r = L / 8, c = (L % 8) ^ swz_v(r);
-    voff[i] = (uint32_t)(r * BN + c * 8) * 2u;
-  }
+  constexpr int PIECE_STEP = 4096;      // halfs between the sources of consecutive pieces of a wave
+  static_assert((NWAVE * 64 / KCH) * D == PIECE_STEP && (NWAVE * 64 / 8) * BN == PIECE_STEP, "piece stride");
   // unit u = { V_u^T, K_{u+1} } goes to stage (u+1) mod 3.  A unit is fetched in NLOAD pieces per
   // wave; the pieces of one unit are spread over a matrix phase (see matrix_stream).
   uint32_t ld_lds = 0;
@@ -135,12 +131,14 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
   auto issue_piece = [&](int n) __attribute__((always_inline)) {
     if (n < U::KPW) {
       const int ins = wave + NWAVE * n;
-      const bool ok = ld_real && ((n + 1) * NWAVE <= U::K_INSTR || ins < U::K_INSTR);
-      gload_lds16_off(ld_kt, koff[n], ok ? ld_lds + (uint32_t)ins * 1024u : dump);
+      const bool have = (n + 1) * NWAVE <= U::K_INSTR || ins < U::K_INSTR;     // (a piece this wave does not have reads piece 0 again)
+      const bool ok = ld_real && have;
+      gload_lds16_off(ld_kt + (have ? n * PIECE_STEP : 0), koff0, ok ? ld_lds + (uint32_t)ins * 1024u : dump);
     } else {
       const int m = n - U::KPW, ins = wave + NWAVE * m;
-      const bool ok = ld_real && ((m + 1) * NWAVE <= U::V_INSTR || ins < U::V_INSTR);
-      gload_lds16_off(ld_vt, voff[m], ok ? ld_lds + (uint32_t)U::KBYTES + (uint32_t)ins * 1024u : dump);
+      const bool have = (m + 1) * NWAVE <= U::V_INSTR || ins < U::V_INSTR;
+      const bool ok = ld_real && have;
+      gload_lds16_off(ld_vt + (have ? m * PIECE_STEP : 0), voff0, ok ? ld_lds + (uint32_t)U::KBYTES + (uint32_t)ins * 1024u : dump);
     }
   };
   auto issue_unit = [&](int u, bool real) __attribute__((always_inline)) {
@@ -209,7 +207,20 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
       ps[kb][n] = __builtin_amdgcn_fdot2(pr2, ones, ps[kb][n], false);
     }
   };
-  auto matrix_stream = [&](const char* bv, const char* bk, auto do2_tag, auto do1_tag, auto ld_tag) __attribute__((always_inline)) {
+  // Operand addresses.  Row 32*y + lq of a K tile, chunk (2*sl + hi) XOR swizzle(lq), is at
+  //   (tile + lq*row_bytes + ((hi ^ swizzle) << 4)) ^ (sl << 5), plus y*32 rows as an immediate:
+  // the XOR only touches the chunk bits because every tile starts at a multiple of the row size.
+  // One per-lane constant per tile kind serves all operands (likewise for V^T, whose chunk is
+  // 4*(t>>1) + (t&1) XOR 2*hi); nothing per-lane has to follow the ring of stages.
+  const uint32_t lane_k = (uint32_t)(lq * (D * 2) + ((hi ^ swz_k<D>(lq)) << 4));
+  const uint32_t lane_v = (uint32_t)(lq * (BN * 2) + (((2 * hi) ^ swz_v(lq)) << 4));
+  static_assert(U::BYTES % (D * 2) == 0 && U::KBYTES % (D * 2) == 0 && U::BYTES % (BN * 2) == 0 && U::KBYTES % (BN * 2) == 0,
+                "tiles start at multiples of their row size");
+  auto lds_rd = [](uint32_t addr) __attribute__((always_inline)) -> half8 {
+    return *reinterpret_cast<const __attribute__((address_space(3))) half8*>((uintptr_t)addr);
+  };
+  auto matrix_stream = [&](uint32_t bv, uint32_t bk, auto do2_tag, auto do1_tag, auto ld_tag) __attribute__((always_inline)) {
+    const uint32_t ak = bk + lane_k, av0 = bv + lane_v;
     constexpr bool DO2 = decltype(do2_tag)::value, DO1 = decltype(do1_tag)::value, LD = decltype(ld_tag)::value;
     constexpr int N2 = DO2 ? 4 * NA2 : 0, N1 = DO1 ? NSLAB * NA1 : 0, NOPS = N2 + N1;
     if (DO1) {
@@ -220,10 +231,10 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
     auto load_op = [&](int k) __attribute__((always_inline)) -> half8 {
       if (k < N2) {
         const int t = k / NA2, x = k % NA2;
-        return lds_v(bv, 32 * x + lq, 4 * (t >> 1) + 2 * hi + (t & 1));
+        return lds_rd((av0 ^ (uint32_t)((4 * (t >> 1) + (t & 1)) << 4)) + (uint32_t)(x * 32 * BN * 2));
       }
       const int kk = k - N2, sl = kk / NA1, y = kk % NA1;
-      return lds_k<D>(bk, 32 * y + lq, 2 * sl + hi);
+      return lds_rd((ak ^ (uint32_t)(sl << 5)) + (uint32_t)(y * 32 * D * 2));
     };
 #pragma unroll
     for (int k = 0; k < RING - 1 && k < NOPS; ++k) buf[k] = load_op(k);
@@ -258,14 +269,14 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
   wait_vmcnt<2 * U::NLOAD>();                     // unit -1 has landed
   phase_barrier();
   if (grp == 1) phase_barrier();
-  if (nj_w > 0) matrix_stream(smem, smem, no{}, yes{}, no{});
+  if (nj_w > 0) matrix_stream(smem_base, smem_base, no{}, yes{}, no{});
   if (grp == 1) wait_vmcnt<U::NLOAD>();           // unit 0
   phase_barrier();
 
   for (int i = 0; i < nj; ++i) {
     const int k0 = i * BN;
     const bool on = i < nj_w;
-    const char* stage = smem + ((i + 1) % NSTAGE) * U::BYTES;
+    const uint32_t stage = smem_base + (uint32_t)((i + 1) % NSTAGE) * U::BYTES;
     const bool tile_has_fault = INJ && fcur < fend && F[fcur].kv_tile == i;
 
     // =========================================================== softmax phase
@@ -506,7 +517,7 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
     prepare_unit(i + 2, i + 2 < nj);
     __builtin_amdgcn_s_setprio(1);
     // (after a wave's last key tile GEMM I runs on a tile it does not need: same code, result unused)
-    if (on) matrix_stream(stage + U::KBYTES, stage, yes{}, yes{}, yes{});
+    if (on) matrix_stream(stage + (uint32_t)U::KBYTES, stage, yes{}, yes{}, yes{});
     else {
 #pragma unroll
       for (int n = 0; n < U::NLOAD; ++n) issue_piece(n);
