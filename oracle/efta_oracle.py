@@ -73,6 +73,17 @@ listed in the design notes of the repository):
   implied one (event CHECK_L).  The range restriction is not applied in this mode.  In the final
   sum-form check the normalised extra fold (row-sum / row-sum = 1) is part of class 0.
 
+* ``per_step`` (the paper's EFTA before the unified-verification optimisation of Section 3.4:
+  every step is verified where it happens).  In each iteration (a) GEMM I is verified on its own:
+  a class whose linear residual exceeds eps1/2 (scale*|R1| > eps1/2) is located and repaired even
+  if the product-form statistic stays below eps1, then the product-form check runs as above and
+  catches what is left (exponentiation faults); (b) after the reduce-sum the row-sum is checked
+  against its range so far (lower bound as above, upper bound the number of unmasked keys seen so
+  far) and replaced by the lower bound when outside; (c) after GEMM II the unnormalised output
+  accumulator is checked against its checksum, |check1 - fold| <= tau_o * row-sum, and a located
+  element is restored.  Events of (b) and (c) carry the key-tile index.  The checks after the loop
+  stay as they are (they cover the normalisation).  Not combined with ``rowsum_fold``.
+
 Thresholds (eps1, tau_o, delta_l) are this repository's choices: the paper's own
 values (0.48 absolute, 7e-6 relative) belong to its one-word fp16 checksums and
 carry a 5.9% false-alarm rate.  Which faults the paper's code would flag at a
@@ -102,6 +113,7 @@ class Params:
     correct: bool = True               # False: detect and locate only
     rowsum_fold: bool = False          # True: the row-sum rides through GEMM II as an extra fold of
                                        # checksum class 0 and is verified / repaired exactly (see below)
+    per_step: bool = False             # True: verification after every step instead of unified (see above)
 
 
 def bitflip32(x: float, bit: int) -> float:
@@ -247,6 +259,10 @@ def efta_rows(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
     events: List[Event] = []
     flipped: List[Tuple[int, float]] = []     # (stage, value before the flip) of every applied fault
     lam_ratio = 0.0
+    lin_ratio = 0.0            # per_step: largest linear residual over its threshold
+    o_step_ratio = 0.0         # per_step: largest per-iteration output residual over its threshold
+    l_step_distance = np.inf   # per_step: smallest relative distance of a row-sum to its range, any iteration
+    assert not (prm.per_step and prm.rowsum_fold)
     n_tiles = (N + Bc - 1) // Bc
 
     for j in range(n_tiles):
@@ -313,6 +329,15 @@ def efta_rows(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
         with np.errstate(invalid="ignore"):
             ok = np.abs(lam) <= prm.eps1
         det = has_valid & ~ok
+        if prm.per_step:
+            with np.errstate(invalid="ignore"):
+                lin_all = ~(sc * np.abs(R1) <= prm.eps1 / 2)
+            det |= has_valid & lin_all
+            finl = has_valid & np.isfinite(R1)
+            if finl.any():
+                lin_ratio = max(lin_ratio, float((sc * np.abs(R1[finl])).max()) / (prm.eps1 / 2))
+            if (has_valid & ~np.isfinite(R1)).any():
+                lin_ratio = np.inf
         fin = has_valid & np.isfinite(lam)
         if fin.any():
             lam_ratio = max(lam_ratio, float(np.abs(lam[fin]).max()) / prm.eps1)
@@ -357,6 +382,40 @@ def efta_rows(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
                 flipped.append((ST_OACC, float(Ot[ri, col])))
                 Ot[ri, col] = bitflip32(Ot[ri, col], bit)
         m[act] = m_new
+        if prm.per_step:
+            # (b) range of the row-sum so far
+            seen = np.minimum(row_idx[act] + 1, min(N, k0 + Bc)) if prm.causal else np.full(act.size, float(min(N, k0 + Bc)))
+            seen = seen.astype(np.float64)
+            la, lo_ = ell[act], lower[act]
+            with np.errstate(all="ignore"):
+                in_rng = (lo_ * (1 - prm.delta_l) <= la) & (la <= seen * (1 + prm.delta_l))
+                dst = np.minimum(np.abs(la / (lo_ * (1 - prm.delta_l)) - 1), np.abs(la / (seen * (1 + prm.delta_l)) - 1))
+            dst = np.where(np.isfinite(dst), dst, np.inf)
+            if dst.size:
+                l_step_distance = min(l_step_distance, float(dst.min()))
+            for i in np.flatnonzero(~in_rng):
+                events.append((CHECK_L, j, int(row_idx[act[i]]), 0))
+                if prm.correct:
+                    ell[act[i]] = lower[act[i]]
+            # (c) GEMM II and the rescale, on the unnormalised accumulator
+            with np.errstate(all="ignore"):
+                f1, _ = fold(Ot[act], s)
+                Rs = Oc1[act] - f1
+                thr = prm.tau_o * ell[act][:, None]
+                okS = np.abs(Rs) <= thr
+                stat = np.abs(Rs) / thr
+            finS = np.isfinite(stat)
+            if finS.any():
+                o_step_ratio = max(o_step_ratio, float(stat[finS].max()))
+            if (~finS).any():
+                o_step_ratio = np.inf
+            for (i, c) in zip(*np.nonzero(~okS)):
+                cols = c + s * np.arange(nV)
+                r = act[i]
+                lstar, val = locate_and_restore(Ot[r, cols], Oc1[r, c], Oc2[r, c])
+                events.append((CHECK_O, j, int(row_idx[r]), int(cols[lstar]) if lstar >= 0 else -1))
+                if prm.correct and lstar >= 0:
+                    Ot[r, cols[lstar]] = val
 
     U = np.minimum(row_idx + 1, N).astype(np.float64) if prm.causal else np.full(n, float(N))
     l_ratio = 0.0
@@ -416,7 +475,8 @@ def efta_rows(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
         if prm.correct and lstar >= 0:
             O[i, cols[lstar]] = val
     diag = {"lambda_ratio": float(lam_ratio), "o_ratio": float(o_ratio),
-            "l_distance": float(dist.min()) if n else np.inf, "l_ratio": float(l_ratio), "flipped": flipped}
+            "l_distance": float(dist.min()) if n else np.inf, "l_ratio": float(l_ratio), "flipped": flipped,
+            "lin_ratio": float(lin_ratio), "o_step_ratio": float(o_step_ratio), "l_step_distance": float(l_step_distance)}
     return O, sorted(events), diag
 
 
@@ -427,11 +487,11 @@ def fault_is_robust(diag: Dict[str, float], band: float = 4.0, l_band: float = 2
     statistic is either below threshold/band or above threshold*band, and the
     final row-sum is further than ``l_band`` (relative) from both range bounds.
     """
-    for key in ("lambda_ratio", "o_ratio", "l_ratio"):
+    for key in ("lambda_ratio", "o_ratio", "l_ratio", "lin_ratio", "o_step_ratio"):
         r = diag.get(key, 0.0)
         if 1.0 / band <= r <= band:
             return False
-    return diag["l_distance"] > l_band
+    return diag["l_distance"] > l_band and diag.get("l_step_distance", np.inf) > l_band
 
 
 def fp32_is_fragile(x: float, stage: int) -> bool:

@@ -462,3 +462,92 @@ def test_rowsum_fold_non_finite_rowsum():
         O, ev, _ = efta_rows(Q, np.arange(N), K, V, prm, [(ST_ROWSUM, 1, 7, 0, bit)])
         assert ev == [(CHECK_L, -1, 7, 0)]
         assert np.abs(O - clean).max() < 1e-10
+
+
+# ---------------------------------------------------------------- per-step verification (EFTA before unification)
+
+@pytest.mark.parametrize("N,d,Bc,causal", [(128, 64, 64, False), (200, 16, 64, True), (77, 8, 16, False), (1, 8, 8, True)])
+def test_per_step_is_silent_and_exact_without_faults(N, d, Bc, causal):
+    """Each step's own identity holds without faults (eq. (15) for GEMM I, the same identity applied
+    to the running accumulator for GEMM II and the rescale, the range of Section 3.4 case 3 at every
+    iteration), so verifying after every step changes nothing and reports nothing."""
+    Q, K, V = _rand(N, d, 170 + N)
+    prm = Params(scale=d ** -0.5, causal=causal, block_n=Bc, per_step=True)
+    O, ev, dg = efta_rows(Q, np.arange(N), K, V, prm)
+    assert ev == []
+    assert np.abs(O - attention_clean(Q, K, V, prm.scale, causal)).max() < 1e-12
+    assert dg["lin_ratio"] < 1e-9 and dg["o_step_ratio"] < 1e-9 and dg["l_step_distance"] > 0
+
+
+def test_per_step_output_identity_is_exact_on_integers():
+    """K = 0 makes every P equal to one, so with integer V the running accumulator and its checksum
+    are exact sums of integers: the per-iteration residual is exactly zero (a threshold at
+    rounding level passes) and any flipped accumulator bit is found in its own iteration and
+    restored exactly."""
+    N, d, Bc = 48, 16, 16
+    rng = np.random.default_rng(171)
+    Q = rng.standard_normal((N, d)); K = np.zeros((N, d)); V = rng.integers(-4, 5, size=(N, d)).astype(np.float64)
+    prm = Params(scale=1.0, causal=False, block_n=Bc, per_step=True, tau_o=1e-12)
+    O, ev, dg = efta_rows(Q, np.arange(N), K, V, prm)
+    assert ev == [] and dg["o_step_ratio"] == 0.0
+    clean = attention_clean(Q, K, V, 1.0, False)
+    for (row, col, kt, bit) in ((0, 0, 0, 23), (17, 15, 1, 30), (47, 9, 2, 3), (5, 8, 1, 31)):
+        _, _, dgu = efta_rows(Q[row:row + 1], np.array([row]), K, V, prm, [(ST_OACC, kt, row, col, bit)])
+        before = dgu["flipped"][0][1]
+        O, ev, _ = efta_rows(Q[row:row + 1], np.array([row]), K, V, prm, [(ST_OACC, kt, row, col, bit)])
+        if bitflip32(before, bit) == before:
+            continue
+        assert ev == [(CHECK_O, kt, row, col)], (row, col, kt, bit, ev)
+        assert np.abs(O[0] - clean[row]).max() < 1e-12
+
+
+def test_per_step_names_the_iteration_unified_does_not():
+    N, d, Bc = 64, 32, 16
+    Q, K, V = _rand(N, d, 172)
+    clean = attention_clean(Q, K, V, 0.3, True)
+    step = Params(scale=0.3, causal=True, block_n=Bc, per_step=True)
+    uni = Params(scale=0.3, causal=True, block_n=Bc)
+    for (row, col, kt, bit) in ((63, 0, 0, 28), (40, 31, 1, 29), (20, 13, 0, 30), (33, 8, 1, 27)):
+        f = [(ST_OACC, kt, row, col, bit)]
+        O, ev, dg = efta_rows(Q, np.arange(N), K, V, step, f)
+        assert dg["o_step_ratio"] > 1
+        assert ev == [(CHECK_O, kt, row, col)]
+        assert np.abs(O - clean).max() < 1e-10
+        O2, ev2, _ = efta_rows(Q, np.arange(N), K, V, uni, f)
+        assert ev2 == [(CHECK_O, -1, row, col)] and np.abs(O2 - clean).max() < 1e-10
+    # a row-sum pushed out of its range is seen in the iteration it happens in
+    f = [(ST_ROWSUM, 1, 50, 0, 30)]
+    O, ev, _ = efta_rows(Q, np.arange(N), K, V, step, f)
+    assert ev == [(CHECK_L, 1, 50, 0)]
+    _, ev2, _ = efta_rows(Q, np.arange(N), K, V, uni, f)
+    assert ev2 == [(CHECK_L, -1, 50, 0)]
+    # the substituted lower bound at iteration 1 is then carried on like the row-sum itself
+    assert np.all(np.isfinite(O)) and np.abs(O[np.arange(N) != 50] - clean[np.arange(N) != 50]).max() < 1e-12
+
+
+def test_per_step_catches_a_linear_fault_the_unified_statistic_lets_pass():
+    """A score error e with eps1/2 < scale*e <= eps1 changes the product-form statistic by less than
+    eps1 (the exponential follows the damaged score, so only the checksum side moves) but exceeds
+    the GEMM I threshold on its own."""
+    N, d, Bc = 32, 16, 16
+    Q, K, V = _rand(N, d, 173)
+    sc = 0.25
+    row, col, kt, bit = 20, 19, 1, 14
+    S = Q[row] @ K[col]
+    e = abs(bitflip32(S, bit) - np.float32(S))
+    eps1 = float(sc * e * 1.5)
+    clean = attention_clean(Q, K, V, sc, False)
+    f = [(ST_S, kt, row, col, bit)]
+    uni = Params(scale=sc, causal=False, block_n=Bc, eps1=eps1)
+    _, ev, dg = efta_rows(Q[row:row + 1], np.array([row]), K, V, uni, f)
+    assert ev == [] and 0.5 < dg["lambda_ratio"] < 1.0
+    step = Params(scale=sc, causal=False, block_n=Bc, eps1=eps1, per_step=True)
+    O, ev, dg = efta_rows(Q[row:row + 1], np.array([row]), K, V, step, f)
+    assert ev == [(CHECK_S, kt, row, col)] and 1.0 < dg["lin_ratio"] < 2.0
+    assert np.abs(O[0] - clean[row]).max() < 1e-6
+
+
+def test_per_step_rejects_the_rowsum_fold():
+    Q, K, V = _rand(16, 8, 174)
+    with pytest.raises(AssertionError):
+        efta_rows(Q, np.arange(16), K, V, Params(scale=1.0, causal=False, block_n=8, per_step=True, rowsum_fold=True))
