@@ -88,6 +88,15 @@ typedef struct {
                              head_dim/8 + 1 folds decides whether the row-sum is the wrong element, and
                              if so it is replaced by the implied one (event FTATTN_CHECK_L).  The range
                              restriction is not applied in this mode. */
+  int32_t per_step;       /* 0: unified verification (Algorithm 1, Section 3.4 "optimized EFTA").
+                             1: verification after every step, the variant the paper measures as EFTA
+                             before that optimisation: in every iteration GEMM I is verified on its own
+                             (a class whose linear residual exceeds eps1/2 is located and repaired even
+                             when the product-form statistic stays below eps1), the row-sum is checked
+                             against its range so far after the reduce-sum, and the unnormalised output
+                             accumulator against its checksum after GEMM II (|residual| <= tau_o *
+                             row-sum); their events carry the key tile.  The checks after the loop stay.
+                             Needs ft_mode FTATTN_FT_CORRECT and rowsum_fold 0. */
   int32_t max_events;     /* capacity of the event log; <= 0 selects 65536 */
   int32_t device;         /* HIP device ordinal */
 } ftattn_config;

@@ -59,8 +59,12 @@ __device__ __forceinline__ void phase_barrier() {
   __builtin_amdgcn_sched_barrier(0);
 }
 
-template <int D, bool FT, bool CAUSAL, bool INJ>
+// PS: verification after every step (the paper's EFTA before the unified verification of
+// Section 3.4): GEMM I is verified on its own in every iteration, the row-sum against its range
+// and the unnormalised output accumulator against its checksum after every GEMM II.
+template <int D, bool FT, bool CAUSAL, bool INJ, bool PS = false>
 __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
+  static_assert(FT || !PS, "per-step verification is a mode of the protected kernel");
   using U = Unit<D, FT>;
   constexpr int NSLAB = D / 16;     // k-slabs of GEMM I
   constexpr int NFB = D / 32;       // 32-feature blocks of O^T
@@ -265,6 +269,82 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
     }
     __builtin_amdgcn_sched_group_barrier(0x008, RING - 1, 0);
   };
+  // Sum-form check of the output accumulator against its checksums (Algorithm 1, last "if"; text
+  // after eq. (16) for location and repair): class r of the lane, folds o[fb][4*gg + r].  `thr` is
+  // the threshold in the units the accumulator is in, `tile` the key tile reported with an event
+  // (-1 after the loop), `xfold` / `xv` the extra fold of class 0 in the exact row-sum mode.
+  float rmax_o = 0.f;
+  auto sum_check = [&](const float thr, const int tile, const bool real, const bool xf, const float xv, const bool track) -> bool {
+    bool bad = false;
+    float R[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      float sum1 = 0.f;
+#pragma unroll
+      for (int fb = 0; fb < NFB; ++fb)
+#pragma unroll
+        for (int gg = 0; gg < 4; ++gg) sum1 += o[fb][4 * gg + r];
+      if (r == 0 && xf) sum1 += xv;      // the normalised extra fold of class 0
+      R[r] = (oc[r] + oc[4 + r]) - sum1;
+      bool d = real && !(__builtin_fabsf(R[r]) <= thr);
+      bad |= d;
+      if (track && !d && real) rmax_o = fmax2(rmax_o, __builtin_fabsf(R[r]));
+    }
+    if (wave_any(bad)) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        if (real && !(__builtin_fabsf(R[r]) <= thr)) {
+          float chk1 = oc[r] + oc[4 + r], chk2 = oc[8 + r] + oc[12 + r];
+          float sum2 = 0.f, big = -1.f;
+          int l_big = -1;
+#pragma unroll
+          for (int fb = 0; fb < NFB; ++fb)
+#pragma unroll
+            for (int gg = 0; gg < 4; ++gg) {
+              float ov = o[fb][4 * gg + r];
+              sum2 += (float)(4 * fb + gg + 1) * ov;
+              float mag = finitef(ov) ? __builtin_fabsf(ov) : __builtin_inff();
+              if (mag > big) { big = mag; l_big = 4 * fb + gg; } else if (mag == big) { l_big = -1; }
+            }
+          const bool xfold = r == 0 && xf;      // class 0 has the row-sum as fold NFOLD_V
+          if (xfold) {
+            sum2 += (float)(NFOLD_V + 1) * xv;
+            float mag = finitef(xv) ? __builtin_fabsf(xv) : __builtin_inff();
+            if (mag > big) { big = mag; l_big = NFOLD_V; } else if (mag == big) { l_big = -1; }
+          }
+          float ratio = (chk2 - sum2) / R[r];
+          int lstar = -1;
+          if (finitef(ratio)) {
+            float c = __builtin_rintf(ratio) - 1.0f;
+            if (c >= 0.f && c < (float)(xfold ? NFOLD_V + 1 : NFOLD_V)) lstar = (int)c;
+          } else {
+            lstar = l_big;
+          }
+          if (xfold && lstar == NFOLD_V) continue;             // the row-sum itself: reported by its own check
+          int col = lstar >= 0 ? 8 * lstar + 4 * hi + r : -1;
+          bool fix = a.correct && lstar >= 0;
+          log_event(a, bh, FTATTN_CHECK_O, tile, row, col, R[r], fix ? 1 : 0);
+          if (fix) {
+            float rest = xfold ? xv : 0.f;
+#pragma unroll
+            for (int fb = 0; fb < NFB; ++fb)
+#pragma unroll
+              for (int gg = 0; gg < 4; ++gg)
+                if (4 * fb + gg != lstar) rest += o[fb][4 * gg + r];
+            float val = chk1 - rest;
+#pragma unroll
+            for (int fb = 0; fb < NFB; ++fb)
+#pragma unroll
+              for (int gg = 0; gg < 4; ++gg)
+                if (4 * fb + gg == lstar) o[fb][4 * gg + r] = val;
+          }
+        }
+      }
+      return true;       // events may have been written
+    }
+    return false;
+  };
+
   // ---- prologue: the first key tile's scores; group 1 starts one barrier later than group 0
   wait_vmcnt<2 * U::NLOAD>();                     // unit -1 has landed
   phase_barrier();
@@ -371,6 +451,15 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
             pr *= ((p[1][r] * p[1][4 + r]) * s2) * ((p[1][8 + r] * p[1][12 + r]) * s2);
             dv[r] = __builtin_fabsf(pr - 1.0f);
             bad |= !(dv[r] <= a.tau_fast);
+            if (PS) {
+              // strided ABFT of GEMM I alone (eq. (15)): same sum order as the exact evaluation below
+              float sum1 = 0.f;
+#pragma unroll
+              for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int gg = 0; gg < 4; ++gg) sum1 += s[kb][4 * gg + r];
+              bad |= !(a.scale * __builtin_fabsf(chk - sum1) <= 0.5f * a.eps1);
+            }
           }
           recheck = wave_any(bad);
           if (recheck) ++rechecks;
@@ -402,10 +491,10 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
               }
             float R1 = chk1 - sum1;
             float lam = LN2 * E - a.scale * R1;
-            bool det = nvalid > 0 && !(__builtin_fabsf(lam) <= a.eps1);
+            const bool linear = !(a.scale * __builtin_fabsf(R1) <= 0.5f * a.eps1);
+            bool det = nvalid > 0 && (!(__builtin_fabsf(lam) <= a.eps1) || (PS && linear));
             if (det) {
               logged = true;
-              bool linear = !(a.scale * __builtin_fabsf(R1) <= 0.5f * a.eps1);
               if (linear) {
                 float chk2 = sc[8 + r] + sc[12 + r];
                 float sum2 = 0.f, big = -1.f;
@@ -553,13 +642,30 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
       }
       while (fcur < fend && F[fcur].kv_tile == i) ++fcur;
     }
+    if (PS && on) {
+      // ---- verification of this iteration's reduce-sum (range so far, Section 3.4 case 3) and of
+      // GEMM II with the rescale (sum-form check on the unnormalised accumulator)
+      const bool real = row < N;
+      float l = sum32(l_part);
+      const int seen = k0 + BN < N ? k0 + BN : N;
+      const float Ub = (float)(CAUSAL && row + 1 < seen ? row + 1 : seen);
+      const bool detl = real && !(l_low * (1.f - a.delta_l) <= l && l <= Ub * (1.f + a.delta_l));
+      if (wave_any(detl)) {
+        if (detl) {
+          if (hi == 0) log_event(a, bh, FTATTN_CHECK_L, i, row, 0, l, a.correct ? 1 : 0);
+          if (a.correct) { l = l_low; l_part = hi ? 0.f : l_low; }
+        }
+        wait_vmcnt<0>();      // the event log's stores complete out of order with loads: drain before the counted waits
+      }
+      if (sum_check(a.tau_o * l, i, real, false, 0.f, false)) wait_vmcnt<0>();
+    }
     if (grp == 1) wait_vmcnt<U::NLOAD>();         // unit i+1 (unit i+2 may still be in flight)
     phase_barrier();
   }
   if (grp == 0) phase_barrier();
 
   // ================= after the loop: row-sum range check, normalisation, sum-form check, store
-  float rmax_o = 0.f, rmax_u = 0.f, rmax_l = 0.f;
+  float rmax_u = 0.f, rmax_l = 0.f;
   {
     const bool real = row < N;
     float l = sum32(l_part);
@@ -627,73 +733,7 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
     for (int fb = 0; fb < NFB; ++fb) o[fb] *= inv;
     if (FT) {
       oc *= inv;
-      bool bad = false;
-      float R[4];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        float sum1 = 0.f;
-#pragma unroll
-        for (int fb = 0; fb < NFB; ++fb)
-#pragma unroll
-          for (int gg = 0; gg < 4; ++gg) sum1 += o[fb][4 * gg + r];
-        if (r == 0 && lfold && hi == 0) sum1 += l * inv;      // the normalised extra fold of class 0
-        R[r] = (oc[r] + oc[4 + r]) - sum1;
-        bool d = real && !(__builtin_fabsf(R[r]) <= a.tau_o);
-        bad |= d;
-        if (!d && real) rmax_o = fmax2(rmax_o, __builtin_fabsf(R[r]));
-      }
-      if (wave_any(bad)) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          if (real && !(__builtin_fabsf(R[r]) <= a.tau_o)) {
-            float chk1 = oc[r] + oc[4 + r], chk2 = oc[8 + r] + oc[12 + r];
-            float sum2 = 0.f, big = -1.f;
-            int l_big = -1;
-#pragma unroll
-            for (int fb = 0; fb < NFB; ++fb)
-#pragma unroll
-              for (int gg = 0; gg < 4; ++gg) {
-                float ov = o[fb][4 * gg + r];
-                sum2 += (float)(4 * fb + gg + 1) * ov;
-                float mag = finitef(ov) ? __builtin_fabsf(ov) : __builtin_inff();
-                if (mag > big) { big = mag; l_big = 4 * fb + gg; } else if (mag == big) { l_big = -1; }
-              }
-            const bool xfold = r == 0 && lfold && hi == 0;      // class 0 has the row-sum as fold NFOLD_V
-            const float xv = l * inv;
-            if (xfold) {
-              sum2 += (float)(NFOLD_V + 1) * xv;
-              float mag = finitef(xv) ? __builtin_fabsf(xv) : __builtin_inff();
-              if (mag > big) { big = mag; l_big = NFOLD_V; } else if (mag == big) { l_big = -1; }
-            }
-            float ratio = (chk2 - sum2) / R[r];
-            int lstar = -1;
-            if (finitef(ratio)) {
-              float c = __builtin_rintf(ratio) - 1.0f;
-              if (c >= 0.f && c < (float)(xfold ? NFOLD_V + 1 : NFOLD_V)) lstar = (int)c;
-            } else {
-              lstar = l_big;
-            }
-            if (xfold && lstar == NFOLD_V) continue;             // the row-sum itself: reported above
-            int col = lstar >= 0 ? 8 * lstar + 4 * hi + r : -1;
-            bool fix = a.correct && lstar >= 0;
-            log_event(a, bh, FTATTN_CHECK_O, -1, row, col, R[r], fix ? 1 : 0);
-            if (fix) {
-              float rest = xfold ? xv : 0.f;
-#pragma unroll
-              for (int fb = 0; fb < NFB; ++fb)
-#pragma unroll
-                for (int gg = 0; gg < 4; ++gg)
-                  if (4 * fb + gg != lstar) rest += o[fb][4 * gg + r];
-              float val = chk1 - rest;
-#pragma unroll
-              for (int fb = 0; fb < NFB; ++fb)
-#pragma unroll
-                for (int gg = 0; gg < 4; ++gg)
-                  if (4 * fb + gg == lstar) o[fb][4 * gg + r] = val;
-            }
-          }
-        }
-      }
+      (void)sum_check(a.tau_o, -1, real, lfold && hi == 0, l * inv, true);
     }
     // ---- store: lane holds features 32*fb + 8*gg + 4*hi + (0..3) of its query
     if (real) {

@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layouts_match_header():
-    assert C.sizeof(ftattn.Config) == 19 * 4
+    assert C.sizeof(ftattn.Config) == 20 * 4
     assert C.sizeof(ftattn.Fault) == 7 * 4
     assert C.sizeof(ftattn.Event) == 8 * 4 == ftattn.EVENT_DTYPE.itemsize
 
@@ -39,7 +39,7 @@ def test_create_rejects_bad_configs_without_a_device():
     def create(**kw):
         base = dict(struct_size=C.sizeof(ftattn.Config), batch=1, heads=1, seq=128, head_dim=64, in_dtype=0, out_dtype=2,
                     causal=0, softmax_scale=0.0, ft_mode=1, stride=8, block_m=0, block_n=0, eps1=0.0, tau_o=0.0,
-                    delta_l=0.0, rowsum_fold=0, max_events=0, device=0)
+                    delta_l=0.0, rowsum_fold=0, per_step=0, max_events=0, device=0)
         base.update(kw)
         cfg = ftattn.Config(**base)
         h = C.c_void_p()
@@ -54,6 +54,9 @@ def test_create_rejects_bad_configs_without_a_device():
     assert create(block_n=128)[0] == ftattn.EUNSUPPORTED
     assert create(ft_mode=5)[0] == ftattn.EINVAL
     assert create(rowsum_fold=2)[0] == ftattn.EINVAL
+    assert create(per_step=2)[0] == ftattn.EINVAL
+    assert create(per_step=1, ft_mode=2)[0] == ftattn.EINVAL       # per-step verification repairs as it goes
+    assert create(per_step=1, rowsum_fold=1)[0] == ftattn.EINVAL
     rc, msg = create(block_m=96)
     assert rc == ftattn.EUNSUPPORTED and "block_m" in msg
     assert lib.ftattn_forward(None, None, None, None, None, None, 0, None) == ftattn.EINVAL
