@@ -83,6 +83,14 @@ listed in the design notes of the repository):
   accumulator is checked against its checksum, |check1 - fold| <= tau_o * row-sum, and a located
   element is restored.  Events of (b) and (c) carry the key-tile index.  The checks after the loop
   stay as they are (they cover the normalisation).  Not combined with ``rowsum_fold``.
+* ``softmax_dmr`` (with ``per_step``; the paper's EFTA protects the softmax by dual modular
+  redundancy, Section 3.1 eq. (11), (12), before SNVR replaces it): maximum, subtraction,
+  exponential and reduce-sum are evaluated twice and compared exactly; where the two differ the
+  step is evaluated again and the value two evaluations agree on is kept.  Under the fault model
+  (one upset, in the named intermediate) this means: every exponential whose stored value differs
+  from its re-evaluation is reported (CHECK_EXP) and replaced, whatever the size of the difference,
+  and a row-sum that differs from its duplicate is reported (CHECK_L, with the key tile) and
+  replaced by the duplicate.  The product-form check and the range restriction are not used.
 
 Thresholds (eps1, tau_o, delta_l) are this repository's choices: the paper's own
 values (0.48 absolute, 7e-6 relative) belong to its one-word fp16 checksums and
@@ -114,6 +122,7 @@ class Params:
     rowsum_fold: bool = False          # True: the row-sum rides through GEMM II as an extra fold of
                                        # checksum class 0 and is verified / repaired exactly (see below)
     per_step: bool = False             # True: verification after every step instead of unified (see above)
+    softmax_dmr: bool = False          # True (needs per_step): softmax protected by duplication, not by SNVR
 
 
 def bitflip32(x: float, bit: int) -> float:
@@ -263,6 +272,7 @@ def efta_rows(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
     o_step_ratio = 0.0         # per_step: largest per-iteration output residual over its threshold
     l_step_distance = np.inf   # per_step: smallest relative distance of a row-sum to its range, any iteration
     assert not (prm.per_step and prm.rowsum_fold)
+    assert prm.per_step or not prm.softmax_dmr
     n_tiles = (N + Bc - 1) // Bc
 
     for j in range(n_tiles):
@@ -329,6 +339,11 @@ def efta_rows(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
         with np.errstate(invalid="ignore"):
             ok = np.abs(lam) <= prm.eps1
         det = has_valid & ~ok
+        if prm.softmax_dmr:
+            # duplication: any stored exponential that differs from its re-evaluation
+            with np.errstate(all="ignore"):
+                differs = touched & valid & (P != np.exp(x))
+            det = differs.reshape(act.size, nK, s).any(axis=1)
         if prm.per_step:
             with np.errstate(invalid="ignore"):
                 lin_all = ~(sc * np.abs(R1) <= prm.eps1 / 2)
@@ -339,10 +354,11 @@ def efta_rows(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
             if (has_valid & ~np.isfinite(R1)).any():
                 lin_ratio = np.inf
         fin = has_valid & np.isfinite(lam)
-        if fin.any():
-            lam_ratio = max(lam_ratio, float(np.abs(lam[fin]).max()) / prm.eps1)
-        if (has_valid & ~np.isfinite(lam)).any():
-            lam_ratio = np.inf
+        if not prm.softmax_dmr:
+            if fin.any():
+                lam_ratio = max(lam_ratio, float(np.abs(lam[fin]).max()) / prm.eps1)
+            if (has_valid & ~np.isfinite(lam)).any():
+                lam_ratio = np.inf
         redo = []
         for (i, c) in zip(*np.nonzero(det)):
             cols = c + s * np.arange(nK)
@@ -372,6 +388,7 @@ def efta_rows(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
             alpha = np.exp(m[act] - m_new)
             ell[act] = alpha * ell[act] + P.sum(axis=1)
             lower[act] = alpha * lower[act] + np.where(np.isfinite(m_hat), np.exp(m_hat - m_new), 0.0)
+            ell_dup = ell.copy()               # the second evaluation of the reduce-sum (softmax_dmr)
             for (ri, col, bit) in by_tile.get((ST_ROWSUM, j), []):
                 flipped.append((ST_ROWSUM, float(ell[ri])))
                 ell[ri] = bitflip32(ell[ri], bit)
@@ -387,16 +404,23 @@ def efta_rows(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
             seen = np.minimum(row_idx[act] + 1, min(N, k0 + Bc)) if prm.causal else np.full(act.size, float(min(N, k0 + Bc)))
             seen = seen.astype(np.float64)
             la, lo_ = ell[act], lower[act]
-            with np.errstate(all="ignore"):
-                in_rng = (lo_ * (1 - prm.delta_l) <= la) & (la <= seen * (1 + prm.delta_l))
-                dst = np.minimum(np.abs(la / (lo_ * (1 - prm.delta_l)) - 1), np.abs(la / (seen * (1 + prm.delta_l)) - 1))
-            dst = np.where(np.isfinite(dst), dst, np.inf)
-            if dst.size:
-                l_step_distance = min(l_step_distance, float(dst.min()))
-            for i in np.flatnonzero(~in_rng):
-                events.append((CHECK_L, j, int(row_idx[act[i]]), 0))
-                if prm.correct:
-                    ell[act[i]] = lower[act[i]]
+            if prm.softmax_dmr:
+                same = (la == ell_dup[act]) | (np.isnan(la) & np.isnan(ell_dup[act]))
+                for i in np.flatnonzero(~same):
+                    events.append((CHECK_L, j, int(row_idx[act[i]]), 0))
+                    if prm.correct:
+                        ell[act[i]] = ell_dup[act[i]]
+            else:
+                with np.errstate(all="ignore"):
+                    in_rng = (lo_ * (1 - prm.delta_l) <= la) & (la <= seen * (1 + prm.delta_l))
+                    dst = np.minimum(np.abs(la / (lo_ * (1 - prm.delta_l)) - 1), np.abs(la / (seen * (1 + prm.delta_l)) - 1))
+                dst = np.where(np.isfinite(dst), dst, np.inf)
+                if dst.size:
+                    l_step_distance = min(l_step_distance, float(dst.min()))
+                for i in np.flatnonzero(~in_rng):
+                    events.append((CHECK_L, j, int(row_idx[act[i]]), 0))
+                    if prm.correct:
+                        ell[act[i]] = lower[act[i]]
             # (c) GEMM II and the rescale, on the unnormalised accumulator
             with np.errstate(all="ignore"):
                 f1, _ = fold(Ot[act], s)
@@ -437,6 +461,8 @@ def efta_rows(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
                 events.append((CHECK_L, -1, int(row_idx[i]), 0))
                 if prm.correct:
                     ell[i] = val
+    elif prm.softmax_dmr:
+        dist = np.full(n, np.inf)
     else:
         # range restriction of the row-sum
         with np.errstate(all="ignore"):

@@ -551,3 +551,53 @@ def test_per_step_rejects_the_rowsum_fold():
     Q, K, V = _rand(16, 8, 174)
     with pytest.raises(AssertionError):
         efta_rows(Q, np.arange(16), K, V, Params(scale=1.0, causal=False, block_n=8, per_step=True, rowsum_fold=True))
+
+
+# ---------------------------------------------------------------- softmax protected by duplication (eq. (11), (12))
+
+def test_dmr_is_silent_and_exact_without_faults():
+    for (N, d, Bc, causal) in ((128, 64, 64, False), (200, 16, 64, True), (1, 8, 8, True)):
+        Q, K, V = _rand(N, d, 270 + N)
+        prm = Params(scale=d ** -0.5, causal=causal, block_n=Bc, per_step=True, softmax_dmr=True)
+        O, ev, _ = efta_rows(Q, np.arange(N), K, V, prm)
+        assert ev == []
+        assert np.abs(O - attention_clean(Q, K, V, prm.scale, causal)).max() < 1e-12
+
+
+def test_dmr_finds_every_changed_exponential_and_rowsum_bit():
+    """Duplication compares exactly: every bit of an exponential or of the row-sum, however small
+    its effect, is reported and the output is the fault-free one; the product-form check and the
+    range restriction (thresholds) let the small ones pass."""
+    N, d, Bc = 48, 16, 16
+    Q, K, V = _rand(N, d, 271)
+    clean = attention_clean(Q, K, V, 0.4, True)
+    dmr = Params(scale=0.4, causal=True, block_n=Bc, per_step=True, softmax_dmr=True)
+    snvr = Params(scale=0.4, causal=True, block_n=Bc, per_step=True)
+    silent_snvr = 0
+    for (row, col, kt) in ((47, 3, 0), (47, 40, 2), (20, 17, 1), (5, 5, 0)):
+        for bit in range(32):
+            f = [(ST_EXP, kt, row, col, bit)]
+            O, ev, _ = efta_rows(Q[row:row + 1], np.array([row]), K, V, dmr, f)
+            assert ev == [(CHECK_EXP, kt, row, col)], (row, col, kt, bit, ev)
+            assert np.abs(O[0] - clean[row]).max() < 1e-12
+            _, ev2, _ = efta_rows(Q[row:row + 1], np.array([row]), K, V, snvr, f)
+            silent_snvr += ev2 == []
+    assert silent_snvr > 20
+    for (row, kt) in ((47, 0), (47, 2), (30, 1)):
+        for bit in range(32):
+            f = [(ST_ROWSUM, kt, row, 0, bit)]
+            O, ev, _ = efta_rows(Q[row:row + 1], np.array([row]), K, V, dmr, f)
+            assert ev == [(CHECK_L, kt, row, 0)]
+            assert np.abs(O[0] - clean[row]).max() < 1e-12
+
+
+def test_dmr_leaves_the_matrix_products_to_their_checksums():
+    N, d, Bc = 64, 32, 16
+    Q, K, V = _rand(N, d, 272)
+    clean = attention_clean(Q, K, V, 0.3, True)
+    dmr = Params(scale=0.3, causal=True, block_n=Bc, per_step=True, softmax_dmr=True)
+    O, ev, _ = efta_rows(Q, np.arange(N), K, V, dmr, [(ST_S, 1, 40, 20, 27), (ST_OACC, 0, 63, 9, 28)])
+    assert ev == [(CHECK_S, 1, 40, 20), (CHECK_O, 0, 63, 9)]
+    assert np.abs(O - clean).max() < 1e-9
+    with pytest.raises(AssertionError):
+        efta_rows(Q, np.arange(N), K, V, Params(scale=0.3, causal=True, block_n=Bc, softmax_dmr=True))
