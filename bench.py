@@ -39,7 +39,7 @@ def measured_traffic(cfg: int):
     return None
 
 
-def time_variant(torch, ftattn, w, tq, tk, tv, ft_mode, steps, warmup, block_m, rowsum_fold=False, per_step=False):
+def time_variant(torch, ftattn, w, tq, tk, tv, ft_mode, steps, warmup, block_m, rowsum_fold=False, per_step=0):
     o = torch.empty((w.batch, w.heads, w.seq, w.head_dim), dtype=torch.float32, device="cuda")
     ctx = ftattn.FtAttn(w.batch, w.heads, w.seq, w.head_dim, w.dtype, w.causal, ft_mode=ft_mode, block_m=block_m,
                         rowsum_fold=rowsum_fold, per_step=per_step)
@@ -205,8 +205,9 @@ def main():
     ap.add_argument("--all-workloads", action="store_true", help="also time workloads 2-4 (extra keys)")
     ap.add_argument("--rowsum-fold", action="store_true",
                     help="attention: protect the row-sum as an extra fold of checksum class 0 (exact check) instead of the range restriction")
-    ap.add_argument("--per-step", action="store_true",
-                    help="attention: verification after every step (the paper's EFTA before unified verification) instead of unified")
+    ap.add_argument("--per-step", type=int, choices=(0, 1, 2), default=0,
+                    help="attention: 1 = verification after every step (the paper's EFTA before unified verification), "
+                         "2 = the same with the softmax protected by duplication; 0 = unified (default)")
     ap.add_argument("--linear", action="store_true",
                     help="time the protected feed-forward GEMM instead of attention (its own JSON line)")
     ap.add_argument("--linear-dtype", choices=("fp16", "bf16"), default="fp16")
@@ -258,7 +259,7 @@ def main():
                                f"{'bf16' if w.dtype else 'fp16'} in, fp32 out, {'causal' if w.causal else 'non-causal'}, fault-free",
                    "block_m": ft["block_m"], "block_n": ft["block_n"], "stride": 8,
                    "rowsum_protection": "extra checksum fold" if args.rowsum_fold else "range restriction",
-                   "verification": "after every step" if args.per_step else "unified"},
+                   "verification": ("unified", "after every step", "after every step, duplicated softmax")[args.per_step]},
         "unprotected_tflops": round(tf_un, 2), "unprotected_ms_per_step": round(un["ms_step"], 4),
         "ft_overhead_pct": round((ft["ms_step"] / un["ms_step"] - 1) * 100, 2),
         "mfma_peak_pct": round(tf / MFMA_PEAK_TFLOPS * 100, 2),

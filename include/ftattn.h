@@ -96,7 +96,13 @@ typedef struct {
                              against its range so far after the reduce-sum, and the unnormalised output
                              accumulator against its checksum after GEMM II (|residual| <= tau_o *
                              row-sum); their events carry the key tile.  The checks after the loop stay.
-                             Needs ft_mode FTATTN_FT_CORRECT and rowsum_fold 0. */
+                             2: as 1, with the softmax protected by duplication (eq. (11), (12)) instead
+                             of the product-form check and the range restriction: maximum, exponentials
+                             and reduce-sum are evaluated twice and compared bit by bit, a third
+                             evaluation settles a difference; every differing exponential is reported
+                             (FTATTN_CHECK_EXP) and replaced, a differing row-sum likewise
+                             (FTATTN_CHECK_L with its key tile).
+                             1 and 2 need ft_mode FTATTN_FT_CORRECT and rowsum_fold 0. */
   int32_t max_events;     /* capacity of the event log; <= 0 selects 65536 */
   int32_t device;         /* HIP device ordinal */
 } ftattn_config;

@@ -77,7 +77,7 @@ static main_fn pick(bool ft, bool causal) {
 // inject: the variant that carries the fault-injection code; calls without a fault list run the
 // variant that has none of it
 // the per-step instantiations live in a translation unit of their own (ftattn_perstep.hip)
-namespace ftattn { void (*select_perstep(int D, bool causal, bool inject))(const KArgs); }
+namespace ftattn { void (*select_perstep(int D, bool causal, bool inject, int mode))(const KArgs); }
 
 static main_fn select_kernel(int D, bool ft, bool causal, bool inject) {
   if (D == 128) return inject ? pick<128, true>(ft, causal) : pick<128, false>(ft, causal);
@@ -105,8 +105,8 @@ extern "C" int ftattn_create(const ftattn_config* cfg, ftattn_ctx** out) {
   if (cfg->block_m != 0 && cfg->block_m != BM) return fail(nullptr, FTATTN_EUNSUPPORTED, "block_m must be 256");
   if (cfg->causal != 0 && cfg->causal != 1) return fail(nullptr, FTATTN_EINVAL, "causal must be 0 or 1");
   if (cfg->rowsum_fold != 0 && cfg->rowsum_fold != 1) return fail(nullptr, FTATTN_EINVAL, "rowsum_fold must be 0 or 1");
-  if (cfg->per_step != 0 && cfg->per_step != 1) return fail(nullptr, FTATTN_EINVAL, "per_step must be 0 or 1");
-  if (cfg->per_step == 1 && (cfg->ft_mode != FTATTN_FT_CORRECT || cfg->rowsum_fold != 0))
+  if (cfg->per_step < 0 || cfg->per_step > 2) return fail(nullptr, FTATTN_EINVAL, "per_step must be 0, 1 or 2");
+  if (cfg->per_step != 0 && (cfg->ft_mode != FTATTN_FT_CORRECT || cfg->rowsum_fold != 0))
     return fail(nullptr, FTATTN_EINVAL, "per_step needs ft_mode FTATTN_FT_CORRECT and rowsum_fold 0");
 
   ftattn_ctx* c = new (std::nothrow) ftattn_ctx();
@@ -167,7 +167,7 @@ extern "C" int ftattn_create(const ftattn_config* cfg, ftattn_ctx** out) {
     }
   if (e.per_step)
     for (int v = 0; v < 4; ++v) {
-      main_fn f = select_perstep(D, (v & 1) != 0, (v >> 1) != 0);
+      main_fn f = select_perstep(D, (v & 1) != 0, (v >> 1) != 0, e.per_step);
       if (!f) { release(c); return fail(nullptr, FTATTN_EUNSUPPORTED, "no kernel for this tile shape"); }
       CREATE_TRY(hipFuncSetAttribute((const void*)f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes(D, true)));
     }
@@ -262,7 +262,7 @@ extern "C" int ftattn_forward(ftattn_ctx* c, const void* q, const void* k, const
   a.fault_off = n_faults > 0 ? c->d_fault_off : nullptr;
   a.events = c->d_events; a.ev_count = c->d_ev_count; a.max_events = e.max_events;
   a.resmax = c->d_resmax; a.recheck = c->d_recheck;
-  main_fn f = e.per_step ? select_perstep(D, e.causal != 0, n_faults > 0) : select_kernel(D, ft, e.causal != 0, n_faults > 0);
+  main_fn f = e.per_step ? select_perstep(D, e.causal != 0, n_faults > 0, e.per_step) : select_kernel(D, ft, e.causal != 0, n_faults > 0);
   if (c->timing) HIP_TRY(c, hipEventRecord(c->ev[1], st));
   hipLaunchKernelGGL(f, dim3(c->BH * c->Ti), dim3(NWAVE * 64), lds_bytes(D, ft), st, a);
   HIP_TRY(c, hipGetLastError());

@@ -59,12 +59,20 @@ __device__ __forceinline__ void phase_barrier() {
   __builtin_amdgcn_sched_barrier(0);
 }
 
-// PS: verification after every step (the paper's EFTA before the unified verification of
+// Value that the compiler must take as new: a second evaluation built on it is not merged with the first.
+__device__ __forceinline__ float opaque(float x) { asm volatile("" : "+v"(x)); return x; }
+__device__ __forceinline__ half2v opaque(half2v x) { asm volatile("" : "+v"(x)); return x; }
+
+// PS >= 1: verification after every step (the paper's EFTA before the unified verification of
 // Section 3.4): GEMM I is verified on its own in every iteration, the row-sum against its range
 // and the unnormalised output accumulator against its checksum after every GEMM II.
-template <int D, bool FT, bool CAUSAL, bool INJ, bool PS = false>
+// PS == 2: in addition the softmax is protected by duplication (eq. (11), (12)) instead of the
+// product-form check and the range restriction: maximum, exponentials and reduce-sum are
+// evaluated twice and compared bit by bit; a third evaluation settles a difference.
+template <int D, bool FT, bool CAUSAL, bool INJ, int PS = 0>
 __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
-  static_assert(FT || !PS, "per-step verification is a mode of the protected kernel");
+  static_assert(FT || PS == 0, "per-step verification is a mode of the protected kernel");
+  constexpr bool DMR = PS == 2;
   using U = Unit<D, FT>;
   constexpr int NSLAB = D / 16;     // k-slabs of GEMM I
   constexpr int NFB = D / 32;       // 32-feature blocks of O^T
@@ -177,6 +185,8 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
   half8 ph[2][2];             // P^T in fp16, B operand of GEMM II: [key block][8-key half]
   float p[2][16];             // exp(S - m) of the key tile in flight, fp32
   float ps[2][2];             // its row-sum, one partial per quarter
+  float ps2[2][2];            // (duplication mode) the second evaluation of the same
+  float l2_part = 0.f, l_prev = 0.f;
   float al = 1.f;             // e^{m_old - m_new} of the key tile in flight
 #pragma unroll
   for (int fb = 0; fb < NFB; ++fb) o[fb] = (float16v)0.f;
@@ -209,7 +219,12 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
       ph[kb][n][x] = pr2[0]; ph[kb][n][x + 1] = pr2[1];
       const half2v ones = {(_Float16)1.f, (_Float16)1.f};
       ps[kb][n] = __builtin_amdgcn_fdot2(pr2, ones, ps[kb][n], false);
+      if (DMR) ps2[kb][n] = __builtin_amdgcn_fdot2(opaque(pr2), ones, x == 0 ? 0.f : ps2[kb][n], false);
     }
+  };
+  // reduce sum (Algorithm 1): one expression for every evaluation, so that they round alike
+  auto rowsum_update = [&](float l_old, const float (&q4)[2][2]) __attribute__((always_inline)) -> float {
+    return l_old * al + ((q4[0][0] + q4[0][1]) + (q4[1][0] + q4[1][1]));
   };
   // Operand addresses.  Row 32*y + lq of a K tile, chunk (2*sl + hi) XOR swizzle(lq), is at
   //   (tile + lq*row_bytes + ((hi ^ swizzle) << 4)) ^ (sl << 5), plus y*32 rows as an immediate:
@@ -249,7 +264,10 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
       if (LD && k % (NOPS / U::NLOAD) == 1 && k / (NOPS / U::NLOAD) < U::NLOAD) issue_piece(k / (NOPS / U::NLOAD));
       const half8 av = buf[k % RING];
       if (DO2 && k < 3 * NA2 && k % NA2 == 0) convert_quarter(k / NA2 + 1);     // one k-step ahead of its use
-      if (DO2 && k == 3 * NA2) l_part = l_part * al + ((ps[0][0] + ps[0][1]) + (ps[1][0] + ps[1][1]));   // reduce sum (Algorithm 1)
+      if (DO2 && k == 3 * NA2) {
+        l_part = rowsum_update(l_part, ps);
+        if (DMR) l2_part = rowsum_update(opaque(l2_part), ps2);
+      }
       if (k < N2) {
         const int t = k / NA2, x = k % NA2;
         if (x < NFB) o[x] = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, ph[t >> 1][t & 1], o[x], 0, 0, 0);
@@ -440,17 +458,49 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
           // exponentials must equal exp2(sl2*check1 - 8*m).  Both sides are divided by that
           // prediction, two factors at a time, so the running product stays near one.
           bool bad = false;
-          float dv[4];
+          float dv[4] = {0.f, 0.f, 0.f, 0.f};
           // (2^(-e/4) per pair of factors, e = sl2*check1 + 8*negm the predicted log2 of the product)
           const float c_chk = sl2 * (-2.0f / NFOLD_K), c_m = -2.0f * negm;
+          if (DMR) {
+            // second evaluation of the maximum and of every exponential (eq. (11), (12)), compared bit
+            // by bit; a third evaluation settles a differing maximum here, a differing exponential in
+            // the exact path below
+            float m0 = fmax2(opaque(s[0][0]), s[0][1]), m1 = fmax2(opaque(s[1][0]), s[1][1]);
+#pragma unroll
+            for (int v = 2; v < 16; v += 2) {
+              m0 = fmax2(fmax2(m0, s[0][v]), s[0][v + 1]);
+              m1 = fmax2(fmax2(m1, s[1][v]), s[1][v + 1]);
+            }
+            const float mxb = max32(fmax2(m0, m1));
+            if (wave_any(as_u(mxb) != as_u(mx))) {
+              float mc = opaque(s[0][0]);
+#pragma unroll
+              for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mc = fmax2(mc, s[kb][v]);
+              mc = max32(mc);
+              if (as_u(mc) == as_u(mxb)) mx = mxb;          // two of three agree on the duplicate
+              m_new = fmax2(m_run, mx);
+              negm = -m_new * sl2;
+              bad = true;                                    // every exponential is looked at again below
+            }
+            uint32_t diff = 0u;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+              for (int v = 0; v < 16; ++v) diff |= as_u(ex2(__builtin_fmaf(opaque(s[kb][v]), sl2, negm))) ^ as_u(p[kb][v]);
+            bad |= diff != 0u;
+          }
 #pragma unroll
           for (int r = 0; r < 4; ++r) {
             float chk = sc[r] + sc[4 + r];
-            float s2 = ex2(__builtin_fmaf(chk, c_chk, c_m));
-            float pr = ((p[0][r] * p[0][4 + r]) * s2) * ((p[0][8 + r] * p[0][12 + r]) * s2);
-            pr *= ((p[1][r] * p[1][4 + r]) * s2) * ((p[1][8 + r] * p[1][12 + r]) * s2);
-            dv[r] = __builtin_fabsf(pr - 1.0f);
-            bad |= !(dv[r] <= a.tau_fast);
+            if (!DMR) {
+              float s2 = ex2(__builtin_fmaf(chk, c_chk, c_m));
+              float pr = ((p[0][r] * p[0][4 + r]) * s2) * ((p[0][8 + r] * p[0][12 + r]) * s2);
+              pr *= ((p[1][r] * p[1][4 + r]) * s2) * ((p[1][8 + r] * p[1][12 + r]) * s2);
+              dv[r] = __builtin_fabsf(pr - 1.0f);
+              bad |= !(dv[r] <= a.tau_fast);
+            }
             if (PS) {
               // strided ABFT of GEMM I alone (eq. (15)): same sum order as the exact evaluation below
               float sum1 = 0.f;
@@ -474,6 +524,7 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
             float chk1 = sc[r] + sc[4 + r];
             float sum1 = 0.f, E = 0.f;
             int nvalid = 0;
+            bool differs = false;       // an exponential that is not what its re-evaluation gives
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -486,13 +537,13 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
                 float pe = ex2(t);
                 if (ok) {
                   ++nvalid;
-                  if (as_u(pe) != as_u(p[kb][v])) E += lg2(p[kb][v]) - t;
+                  if (as_u(pe) != as_u(p[kb][v])) { E += lg2(p[kb][v]) - t; differs = true; }
                 }
               }
             float R1 = chk1 - sum1;
             float lam = LN2 * E - a.scale * R1;
             const bool linear = !(a.scale * __builtin_fabsf(R1) <= 0.5f * a.eps1);
-            bool det = nvalid > 0 && (!(__builtin_fabsf(lam) <= a.eps1) || (PS && linear));
+            bool det = nvalid > 0 && (DMR ? (linear || differs) : (!(__builtin_fabsf(lam) <= a.eps1) || (PS && linear)));
             if (det) {
               logged = true;
               if (linear) {
@@ -606,6 +657,7 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
     prepare_unit(i + 2, i + 2 < nj);
     __builtin_amdgcn_s_setprio(1);
     // (after a wave's last key tile GEMM I runs on a tile it does not need: same code, result unused)
+    if (DMR) l_prev = l_part;
     if (on) matrix_stream(stage + (uint32_t)U::KBYTES, stage, yes{}, yes{}, yes{});
     else {
 #pragma unroll
@@ -649,7 +701,35 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
       float l = sum32(l_part);
       const int seen = k0 + BN < N ? k0 + BN : N;
       const float Ub = (float)(CAUSAL && row + 1 < seen ? row + 1 : seen);
-      const bool detl = real && !(l_low * (1.f - a.delta_l) <= l && l <= Ub * (1.f + a.delta_l));
+      if (DMR) {
+        // the two evaluations of the reduce-sum; a third one, from the fp16 P still in registers,
+        // settles a difference
+        const bool dl = as_u(l_part) != as_u(l2_part);
+        if (wave_any(real && dl)) {
+          float q3[2][2];
+          const half2v ones = {(_Float16)1.f, (_Float16)1.f};
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int n = 0; n < 2; ++n) {
+              q3[kb][n] = 0.f;
+#pragma unroll
+              for (int x = 0; x < 8; x += 2) {
+                half2v pr2 = {ph[kb][n][x], ph[kb][n][x + 1]};
+                q3[kb][n] = __builtin_amdgcn_fdot2(opaque(pr2), ones, q3[kb][n], false);
+              }
+            }
+          const float l3 = rowsum_update(opaque(l_prev), q3);
+          const bool row_dl = dl | (xchg32(dl ? 1.f : 0.f, hi) != 0.f);
+          if (real && row_dl && hi == 0) log_event(a, bh, FTATTN_CHECK_L, i, row, 0, l, a.correct ? 1 : 0);
+          if (a.correct && dl) {
+            if (as_u(l3) == as_u(l2_part)) l_part = l2_part; else if (as_u(l3) == as_u(l_part)) l2_part = l_part;
+          }
+          l = sum32(l_part);
+          wait_vmcnt<0>();    // the event log's stores complete out of order with loads: drain before the counted waits
+        }
+      }
+      const bool detl = !DMR && real && !(l_low * (1.f - a.delta_l) <= l && l <= Ub * (1.f + a.delta_l));
       if (wave_any(detl)) {
         if (detl) {
           if (hi == 0) log_event(a, bh, FTATTN_CHECK_L, i, row, 0, l, a.correct ? 1 : 0);
@@ -718,7 +798,7 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
       const float lp = xchg32(l, hi);
       if (hi == 1) l = lp;
     }
-    if (FT && !lfold) {
+    if (FT && !lfold && !DMR) {
       float Ub = CAUSAL ? (float)(row + 1 < N ? row + 1 : N) : (float)N;
       float lo = l_low;
       bool detl = real && !(lo * (1.f - a.delta_l) <= l && l <= Ub * (1.f + a.delta_l));

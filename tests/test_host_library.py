@@ -54,7 +54,8 @@ def test_create_rejects_bad_configs_without_a_device():
     assert create(block_n=128)[0] == ftattn.EUNSUPPORTED
     assert create(ft_mode=5)[0] == ftattn.EINVAL
     assert create(rowsum_fold=2)[0] == ftattn.EINVAL
-    assert create(per_step=2)[0] == ftattn.EINVAL
+    assert create(per_step=3)[0] == ftattn.EINVAL
+    assert create(per_step=2, ft_mode=2)[0] == ftattn.EINVAL
     assert create(per_step=1, ft_mode=2)[0] == ftattn.EINVAL       # per-step verification repairs as it goes
     assert create(per_step=1, rowsum_fold=1)[0] == ftattn.EINVAL
     rc, msg = create(block_m=96)
