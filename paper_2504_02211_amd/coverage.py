@@ -73,10 +73,12 @@ def _to_torch(bits: np.ndarray, dtype: int):
 class Runner:
     """Keeps the operands on the device and runs one forward call per threshold setting."""
 
-    def __init__(self, q: np.ndarray, k: np.ndarray, v: np.ndarray, dtype: int, causal: bool, rowsum_fold: bool = False):
+    def __init__(self, q: np.ndarray, k: np.ndarray, v: np.ndarray, dtype: int, causal: bool, rowsum_fold: bool = False,
+                 per_step: int = 0):
         import torch
         self.torch = torch
         self.rowsum_fold = rowsum_fold
+        self.per_step = per_step
         self.shape = q.shape
         self.dtype, self.causal = dtype, causal
         self.tq, self.tk, self.tv = (_to_torch(x, dtype) for x in (q, k, v))
@@ -85,7 +87,8 @@ class Runner:
         torch = self.torch
         B, H, N, d = self.shape
         ctx = ftattn.FtAttn(B, H, N, d, self.dtype, self.causal, ft_mode=ft_mode, max_events=1 << 20,
-                            rowsum_fold=self.rowsum_fold, **thresholds)
+                            rowsum_fold=self.rowsum_fold,
+                            per_step=self.per_step if ft_mode == ftattn.FT_CORRECT else 0, **thresholds)
         o = torch.empty((B, H, N, d), dtype=torch.float32, device="cuda")
         ctx.forward(self.tq, self.tk, self.tv, o, faults, torch.cuda.current_stream().cuda_stream)
         rep = ctx.report()
@@ -187,11 +190,11 @@ def draw_ber_faults(batch: int, heads: int, seq: int, head_dim: int, causal: boo
 
 
 def ber_sweep(q: np.ndarray, k: np.ndarray, v: np.ndarray, dtype: int, causal: bool, bers: Sequence[float],
-              seed: int, rowsum_fold: bool = False) -> List[Dict[str, object]]:
+              seed: int, rowsum_fold: bool = False, per_step: int = 0) -> List[Dict[str, object]]:
     """For every bit error rate: how many rows the flips damage when nothing protects them, how
     many of those rows raise an event under protection, and how many are back within the
     tolerance after correction (default thresholds)."""
-    r = Runner(q, k, v, dtype, causal, rowsum_fold)
+    r = Runner(q, k, v, dtype, causal, rowsum_fold, per_step)
     B, H, N, d = q.shape
     clean, _, cfg = r.run(None, ftattn.FT_OFF)
     rows_out = []
@@ -275,6 +278,9 @@ def main() -> None:
     ap.add_argument("--seed", type=lambda s: int(s, 0), default=0xC0FE)
     ap.add_argument("--rowsum-fold", action="store_true",
                     help="protect the row-sum as an extra fold of checksum class 0 (exact check) instead of the range restriction")
+    ap.add_argument("--per-step", type=int, choices=(0, 1, 2), default=0,
+                    help="bit-error-rate sweep: 1 = verification after every step, 2 = the same with the softmax "
+                         "protected by duplication (0 = unified verification)")
     ap.add_argument("--ber", type=float, nargs="*", default=None,
                     help="run the bit-error-rate sweep at these rates instead of the threshold sweep")
     args = ap.parse_args()
@@ -286,8 +292,9 @@ def main() -> None:
         print(f"workload: batch {args.batch}, heads {args.heads}, seq {args.seq}, head_dim {args.head_dim}, {args.dtype}, "
               f"{'non-causal' if args.non_causal else 'causal'}, N(0,1) inputs, seed {args.seed:#x}; "
               f"{population(*shape, not args.non_causal, 64)} fp32 intermediates per pass; row-sum protection: "
-              f"{'extra checksum fold' if args.rowsum_fold else 'range restriction'}")
-        print(ber_markdown(ber_sweep(q, k, v, dtype, not args.non_causal, bers, args.seed + 2, args.rowsum_fold)))
+              f"{'extra checksum fold' if args.rowsum_fold else 'range restriction'}; verification: "
+              f"{('unified', 'after every step', 'after every step, duplicated softmax')[args.per_step]}")
+        print(ber_markdown(ber_sweep(q, k, v, dtype, not args.non_causal, bers, args.seed + 2, args.rowsum_fold, args.per_step)))
         return
     faults = draw_faults(*shape, not args.non_causal, 64, args.faults_per_head, args.seed + 1)
     res = sweep(q, k, v, dtype, not args.non_causal, faults)
