@@ -409,10 +409,18 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
         mx = max32(fmax2(m0, m1));
         m_new = fmax2(m_run, mx);
         negm = -m_new * sl2;
+        // all 32 arguments first, then all 32 exponentials, in place: neighbouring instructions are
+        // independent, where (argument, exponential) pairs through one temporary would each wait
+        // for the other
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-          for (int v = 0; v < 16; ++v) p[kb][v] = ex2(__builtin_fmaf(s[kb][v], sl2, negm));
+          for (int v = 0; v < 16; ++v) p[kb][v] = __builtin_fmaf(s[kb][v], sl2, negm);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) p[kb][v] = ex2(p[kb][v]);
       } else {
         // ============ same with the causal / sequence-end mask applied per element
         mx = -__builtin_inff();
@@ -498,8 +506,8 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
               float s2 = ex2(__builtin_fmaf(chk, c_chk, c_m));
               float pr = ((p[0][r] * p[0][4 + r]) * s2) * ((p[0][8 + r] * p[0][12 + r]) * s2);
               pr *= ((p[1][r] * p[1][4 + r]) * s2) * ((p[1][8 + r] * p[1][12 + r]) * s2);
-              dv[r] = __builtin_fabsf(pr - 1.0f);
-              bad |= !(dv[r] <= a.tau_fast);
+              dv[r] = pr - 1.0f;
+              bad |= !(__builtin_fabsf(dv[r]) <= a.tau_fast);
             }
             if (PS) {
               // strided ABFT of GEMM I alone (eq. (15)): same sum order as the exact evaluation below
@@ -513,7 +521,11 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
           }
           recheck = wave_any(bad);
           if (recheck) ++rechecks;
-          else dev_max = fmax2(fmax2(fmax2(dev_max, dv[0]), fmax2(dv[1], dv[2])), dv[3]);   // largest deviation that passed
+          else {
+            // largest deviation that passed (two three-input maxima; the values are finite here)
+            asm("v_max3_f32 %0, %0, |%1|, |%2|" : "+v"(dev_max) : "v"(dv[0]), "v"(dv[1]));
+            asm("v_max3_f32 %0, %0, |%1|, |%2|" : "+v"(dev_max) : "v"(dv[2]), "v"(dv[3]));
+          }
         }
         if (recheck) {
           // ============ exact re-evaluation (rare: a fast check tripped, or the tile is masked).
