@@ -37,6 +37,14 @@ Readings where the paper is silent:
 * Restoring is done by reconstruction (checksum minus the other folds), and a non-finite
   residual ratio names the fold of overwhelming magnitude, as in the attention oracle.
 * Output columns beyond N in the last block count as zero weight rows.
+* ``fold_tokens`` (the column-checksum counterpart: the paper encodes one operand, K^T in
+  attention, and names the other side only to reject its memory cost there, Section 3.3): the
+  tensor checksums are taken over the token rows of X instead of the weight rows, in blocks of
+  ``block_n`` tokens, so that for every output feature the stride-s fold of Y over the tokens of a
+  block equals X_check W^T.  This is the same method applied to Y^T = W X^T, and it is computed
+  exactly so: operands swapped, faults and events with rows and columns exchanged.  It repairs
+  several errors in one token row (they fall into different columns) and fails on two errors of one
+  output feature whose tokens are a multiple of s apart: the mirror image of the default.
 """
 from __future__ import annotations
 
@@ -54,6 +62,7 @@ class Params:
     tau_abs: float = 0.0
     correct: bool = True        # False: detect and locate only
     bf16: bool = False          # the checksum words are bf16 (inputs are bf16) instead of fp16
+    fold_tokens: bool = False   # checksums over the token rows of X (blocks of block_n tokens) instead of W
 
 
 Fault = Tuple[int, int, int]    # (row, col, bit) of the fp32 accumulator of Y
@@ -108,6 +117,11 @@ def ftgemm(X: np.ndarray, W: np.ndarray, prm: Params, faults: Sequence[Fault] = 
     the fault selector of the tests, the smallest distance (as a ratio) of any check statistic
     to its threshold and the values that were flipped.
     """
+    if prm.fold_tokens:
+        # the same method on Y^T = W X^T: W rows take the place of the tokens, X rows that of the weights
+        swapped = dataclasses.replace(prm, fold_tokens=False)
+        Yt, ev_t, diag = ftgemm(W, X, swapped, [(c, r, b) for (r, c, b) in faults])
+        return np.ascontiguousarray(Yt.T), sorted((c, r, a) for (r, c, a) in ev_t), diag
     M, K = X.shape
     N = W.shape[0]
     s, bn = prm.stride, prm.block_n

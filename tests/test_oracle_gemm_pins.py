@@ -176,3 +176,70 @@ def test_threshold_is_relative_to_the_summed_magnitude():
     Y, ev, _ = orc.ftgemm(X, W, prm, [(3, 10, 22)])
     assert ev == [(3, 10, 1)]
     assert np.max(np.abs(Y - Yref)) < 1e-5
+
+
+# ---------------------------------------------------------------- checksums over the tokens (fold_tokens)
+
+def test_fold_tokens_identity_against_loops():
+    """For every output feature the stride-8 fold of Y over the tokens of a block equals
+    (fold of the token rows of X) W^T: checked with explicit loops on integers, where it is exact."""
+    rng = np.random.default_rng(40)
+    M, N, K = 64, 5, 8
+    X, W = small_ints(rng, (M, K)), small_ints(rng, (N, K))
+    Y = orc.linear_clean(X, W)
+    for c in range(8):
+        xc = sum(X[c + 8 * l] for l in range(M // 8))
+        for n in range(N):
+            assert sum(Y[c + 8 * l, n] for l in range(M // 8)) == float(xc @ W[n])
+    prm = orc.Params(block_n=64, tau_rel=0.0, tau_abs=0.0, fold_tokens=True)
+    Y2, ev, _ = orc.ftgemm(X, W, prm)
+    assert ev == [] and np.array_equal(Y2, Y)
+
+
+def test_fold_tokens_locates_along_the_token_axis():
+    rng = np.random.default_rng(41)
+    M, N, K = 512, 3, 8
+    X, W = small_ints(rng, (M, K), 1, 4), small_ints(rng, (N, K), 1, 4)
+    Yref = X @ W.T
+    prm = orc.Params(tau_rel=0.0, tau_abs=0.25, fold_tokens=True)
+    for row in (0, 7, 8, 255, 256, 300, 511):
+        col = row % N
+        Y, ev, _ = orc.ftgemm(X, W, prm, [(row, col, 23)])
+        assert ev == [(row, col, 1)], (row, ev)
+        assert np.array_equal(Y, Yref)
+
+
+def test_fold_tokens_is_the_mirror_image_of_the_default():
+    """Several errors in one token row are repaired (they lie in different output features, each
+    with its own checksums); two errors of one feature 8 tokens apart are seen but not repaired.
+    The default encoding behaves the other way round on the same faults."""
+    rng = np.random.default_rng(42)
+    M, N, K = 256, 256, 8
+    X, W = small_ints(rng, (M, K), 1, 4), small_ints(rng, (N, K), 1, 4)
+    Yref = X @ W.T
+    tok = orc.Params(tau_rel=0.0, tau_abs=0.25, fold_tokens=True)
+    feat = orc.Params(tau_rel=0.0, tau_abs=0.25)
+    same_row = [(5, 3, 23), (5, 3 + 8 * 9, 23)]          # one token, features 72 apart
+    Y, ev, _ = orc.ftgemm(X, W, tok, same_row)
+    assert sorted(e[:2] for e in ev) == [(5, 3), (5, 75)] and np.array_equal(Y, Yref)
+    Y, ev, _ = orc.ftgemm(X, W, feat, same_row)
+    assert len(ev) == 1 and not np.array_equal(Y, Yref)
+    same_col = [(5, 3, 23), (5 + 8 * 4, 3, 23)]          # one feature, tokens 32 apart
+    Y, ev, _ = orc.ftgemm(X, W, tok, same_col)
+    assert len(ev) == 1 and ev[0][1] == 3 and not np.array_equal(Y, Yref)
+    Y, ev, _ = orc.ftgemm(X, W, feat, same_col)
+    assert sorted(e[:2] for e in ev) == [(5, 3), (37, 3)] and np.array_equal(Y, Yref)
+
+
+def test_fold_tokens_ragged_block_and_random_data():
+    rng = np.random.default_rng(43)
+    M, N, K = 256 + 43, 7, 64
+    X = rng.standard_normal((M, K)).astype(np.float16).astype(np.float64)
+    W = (rng.standard_normal((N, K)) / 8).astype(np.float16).astype(np.float64)
+    prm = orc.Params(fold_tokens=True)
+    Yref = X @ W.T
+    Y, ev, dg = orc.ftgemm(X, W, prm)
+    assert ev == [] and dg["res_max"] < 0.05 and np.array_equal(Y, Yref)
+    Y, ev, _ = orc.ftgemm(X, W, prm, [(M - 1, 6, 22), (10, 0, 30)])
+    assert [e[:2] for e in ev] == [(10, 0), (M - 1, 6)]
+    assert np.max(np.abs(Y - Yref)) < 1e-5
