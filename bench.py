@@ -126,7 +126,7 @@ def bench_linear(args):
     flops = 2.0 * m * n * k
     res = {}
     for name, mode in (("ft", ftgemm.FT_CORRECT), ("off", ftgemm.FT_OFF)):
-        ctx = ftgemm.FtGemm(m, n, k, out_dtype=dt, ft_mode=mode, in_dtype=dt)
+        ctx = ftgemm.FtGemm(m, n, k, out_dtype=dt, ft_mode=mode, in_dtype=dt, fold_tokens=args.fold_tokens)
         stream = torch.cuda.Stream()
         sp = stream.cuda_stream
         ctx.set_timing(True)
@@ -159,7 +159,8 @@ def bench_linear(args):
            "ms_per_step": round(ft["ms_step"], 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": args.linear_dtype.replace("fp", "f"), "data": "synthetic",
            "config": {"workload": f"feed-forward up-projection: {m} tokens, {k} -> {n} features, {args.linear_dtype} in, {args.linear_dtype} out, "
-                                  f"fault-free", "block_n": 256, "stride": 8},
+                                  f"fault-free", "block_n": 256, "stride": 8,
+                      "checksums": "over token rows, encoded per call" if args.fold_tokens else "over weight rows, encoded once"},
            "unprotected_tflops": round(flops / un["ms_step"] / 1e9, 2),
            "unprotected_ms_per_step": round(un["ms_step"], 4),
            "ft_overhead_pct": round((ft["ms_step"] / un["ms_step"] - 1) * 100, 2),
@@ -211,6 +212,8 @@ def main():
     ap.add_argument("--linear", action="store_true",
                     help="time the protected feed-forward GEMM instead of attention (its own JSON line)")
     ap.add_argument("--linear-dtype", choices=("fp16", "bf16"), default="fp16")
+    ap.add_argument("--fold-tokens", action="store_true",
+                    help="linear layer: tensor checksums over the token rows (encoded in every call) instead of the weight rows")
     ap.add_argument("--pmc-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (calibration of HBM byte counters under rocprofv3 --pmc)")
     args = ap.parse_args()

@@ -55,6 +55,13 @@ typedef struct {
   float tau_rel;         /* a class is flagged when |check1 - fold| > tau_abs + tau_rel * sum |Y_l|, */
   float tau_abs;         /* or when that residual is not finite.  tau_rel <= 0 selects 2^-15;
                             tau_abs < 0 selects 0 */
+  int32_t fold_tokens;   /* 0: tensor checksums over the weight rows (blocks of 256 output features), encoded
+                            once per weight matrix by ftgemm_encode_weights.  1: the column-checksum
+                            counterpart (Section 3.3 names it for attention and rejects its memory cost there):
+                            checksums over the token rows of x in blocks of 256 tokens, encoded inside every
+                            ftgemm_forward; the same method on Y^T = W X^T.  It repairs several errors of one
+                            token (they lie in different features) and cannot repair two errors of one feature
+                            whose tokens are a multiple of 8 apart.  ftgemm_encode_weights is not needed. */
   int32_t max_events;    /* capacity of the event log; <= 0 selects 65536 */
   int32_t device;        /* HIP device ordinal */
 } ftgemm_config;
@@ -65,7 +72,8 @@ typedef struct { int32_t row, col, bit; } ftgemm_fault;
 
 typedef struct {
   int32_t row;           /* token index */
-  int32_t col;           /* located output feature; -1 = flagged but not locatable */
+  int32_t col;           /* located output feature; -1 = flagged but not locatable (with fold_tokens it is the
+                            row that is -1 then: the feature is known, the token is not) */
   float residual;        /* check1 - fold of the flagged class */
   int32_t action;        /* 1 restored, 0 detected only */
 } ftgemm_event;

@@ -76,7 +76,10 @@ extern "C" int ftgemm_create(const ftgemm_config* cfg, ftgemm_ctx** out) {
   if (cfg->ft_mode < 0 || cfg->ft_mode > 2) return gfail(nullptr, FTGEMM_EINVAL, "ft_mode out of range");
   if (cfg->stride != 0 && cfg->stride != 8) return gfail(nullptr, FTGEMM_EUNSUPPORTED, "stride must be 8");
   if (cfg->block_n != 0 && cfg->block_n != GBN) return gfail(nullptr, FTGEMM_EUNSUPPORTED, "block_n must be 256");
-  const long long tm = ((long long)cfg->m + GBM - 1) / GBM, tn = ((long long)cfg->n + GBN - 1) / GBN;
+  if (cfg->fold_tokens != 0 && cfg->fold_tokens != 1) return gfail(nullptr, FTGEMM_EINVAL, "fold_tokens must be 0 or 1");
+  // with fold_tokens the kernel runs the transposed problem: its tokens are the weight rows, its features the token rows
+  const long long km = cfg->fold_tokens ? cfg->n : cfg->m, kn = cfg->fold_tokens ? cfg->m : cfg->n;
+  const long long tm = (km + GBM - 1) / GBM, tn = (kn + GBN - 1) / GBN;
   if (tm * tn > 0x7FFFFFFFll) return gfail(nullptr, FTGEMM_EUNSUPPORTED, "too many output tiles");
   // the per-lane load offsets are 32-bit: 256 rows of k fp16 values must fit
   if ((long long)cfg->k * 2 * 256 > 0x7FFFFFFFll) return gfail(nullptr, FTGEMM_EUNSUPPORTED, "k too large");
@@ -135,6 +138,7 @@ extern "C" int ftgemm_encode_weights(ftgemm_ctx* c, const void* w, void* hip_str
   if (!c) return FTGEMM_EINVAL;
   if (!w || ((uintptr_t)w & 15)) return gfail(c, FTGEMM_EINVAL, "w must be a 16-byte aligned device pointer");
   const ftgemm_config& e = c->cfg;
+  if (e.fold_tokens) return FTGEMM_OK;      // the checksums are those of x, taken inside every forward
   GHIP_TRY(c, hipSetDevice(e.device));
   hipStream_t st = (hipStream_t)hip_stream;
   dim3 grid(c->Tn, (e.k / 8 + 31) / 32);
@@ -154,7 +158,8 @@ extern "C" int ftgemm_forward(ftgemm_ctx* c, const void* x, const void* w, void*
   if (n_faults > c->fault_cap) return gfail(c, FTGEMM_EINVAL, "too many faults (limit 65536)");
   const ftgemm_config& e = c->cfg;
   const bool ft = e.ft_mode != FTGEMM_FT_OFF;
-  if (ft && c->encoded_w != w) return gfail(c, FTGEMM_ESTATE, "ftgemm_encode_weights has not been called for this weight matrix");
+  const bool tr = e.fold_tokens != 0;
+  if (ft && !tr && c->encoded_w != w) return gfail(c, FTGEMM_ESTATE, "ftgemm_encode_weights has not been called for this weight matrix");
   hipStream_t st = (hipStream_t)hip_stream;
   GHIP_TRY(c, hipSetDevice(e.device));
   for (int i = 0; i < n_faults; ++i) {
@@ -164,7 +169,7 @@ extern "C" int ftgemm_forward(ftgemm_ctx* c, const void* x, const void* w, void*
       snprintf(msg, sizeof msg, "fault %d (row=%d col=%d bit=%d) is outside the matrix", i, f.row, f.col, f.bit);
       return gfail(c, FTGEMM_EINVAL, msg);
     }
-    c->h_faults[i] = GFault{f.row, f.col, f.bit};
+    c->h_faults[i] = tr ? GFault{f.col, f.row, f.bit} : GFault{f.row, f.col, f.bit};
   }
   if (n_faults > 0) {
     GHIP_TRY(c, hipMemcpyAsync(c->d_faults, c->h_faults, sizeof(GFault) * n_faults, hipMemcpyHostToDevice, st));
@@ -172,12 +177,20 @@ extern "C" int ftgemm_forward(ftgemm_ctx* c, const void* x, const void* w, void*
   }
   ftgemm_reset<<<1, 64, 0, st>>>(c->d_ev_count, c->d_resmax);
 
+  if (ft && tr) {
+    // tensor checksums of this call's token rows (eq. (13), (14) on x)
+    dim3 grid(c->Tn, (e.k / 8 + 31) / 32);
+    if (e.in_dtype == FTGEMM_BF16) ftgemm_encode_w<true><<<grid, 256, 0, st>>>(reinterpret_cast<const uint16_t*>(x), c->wc, e.m, e.k);
+    else ftgemm_encode_w<false><<<grid, 256, 0, st>>>(reinterpret_cast<const uint16_t*>(x), c->wc, e.m, e.k);
+    GHIP_TRY(c, hipGetLastError());
+  }
   GArgs a;
-  a.x = reinterpret_cast<const uint16_t*>(x);
-  a.w = reinterpret_cast<const uint16_t*>(w);
+  a.x = reinterpret_cast<const uint16_t*>(tr ? w : x);
+  a.w = reinterpret_cast<const uint16_t*>(tr ? x : w);
   a.wc = c->wc;
   a.y = y; a.out_dtype = e.out_dtype;
-  a.M = e.m; a.N = e.n; a.K = e.k; a.Tm = c->Tm; a.Tn = c->Tn;
+  a.M = tr ? e.n : e.m; a.N = tr ? e.m : e.n; a.K = e.k; a.Tm = c->Tm; a.Tn = c->Tn;
+  a.transposed = tr ? 1 : 0;
   a.tau_rel = e.tau_rel; a.tau_abs = e.tau_abs;
   a.correct = e.ft_mode == FTGEMM_FT_CORRECT ? 1 : 0;
   a.faults = c->d_faults; a.n_faults = n_faults;

@@ -72,6 +72,8 @@ struct GArgs {
   int32_t* ev_count;
   int32_t max_events;
   uint32_t* resmax;        // float bits of a non-negative value
+  int32_t transposed;      // 1: the kernel's (token, feature) is the caller's (column, row) of Y: checksums over the
+                           // caller's token rows; results are stored, and events named, with the two exchanged
 };
 
 template <bool FT> struct GStage {
@@ -132,7 +134,7 @@ __device__ __forceinline__ void log_gemm_event(const GArgs& a, int row, int col,
   int idx = atomicAdd(a.ev_count, 1);
   if (idx < a.max_events) {
     ftgemm_event e;
-    e.row = row; e.col = col; e.residual = res; e.action = action;
+    e.row = a.transposed ? col : row; e.col = a.transposed ? row : col; e.residual = res; e.action = action;
     a.events[idx] = e;
   }
 }
@@ -344,7 +346,20 @@ __global__ __launch_bounds__(GWAVES * 64) void ftgemm_main(const GArgs a) {
   }
 
   // ---- store: the lane holds features n0 + 32*y + 8*g + 4*hi + (0..3) of its token
-  if (real) {
+  if (real && a.transposed) {
+    // Y is [N][M] seen from here: consecutive lanes (tokens) write consecutive elements of one row
+#pragma unroll
+    for (int y = 0; y < 8; ++y)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int col = n0 + 32 * y + 8 * (v >> 2) + 4 * hi + (v & 3);
+        if (col < N) {
+          const size_t at = (size_t)col * M + row;
+          if (a.out_dtype == FTGEMM_F32) reinterpret_cast<float*>(a.y)[at] = acc[y][v];
+          else reinterpret_cast<uint16_t*>(a.y)[at] = from_f32<BF>(acc[y][v]);
+        }
+      }
+  } else if (real) {
     const size_t base = (size_t)row * N;
     const bool vec = (N & 3) == 0;
 #pragma unroll

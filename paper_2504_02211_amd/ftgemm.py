@@ -24,8 +24,8 @@ EXPORTS = ("ftgemm_create", "ftgemm_get_config", "ftgemm_encode_weights", "ftgem
 class Config(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("m", C.c_int32), ("n", C.c_int32), ("k", C.c_int32),
                 ("in_dtype", C.c_int32), ("out_dtype", C.c_int32), ("ft_mode", C.c_int32), ("stride", C.c_int32),
-                ("block_n", C.c_int32), ("tau_rel", C.c_float), ("tau_abs", C.c_float), ("max_events", C.c_int32),
-                ("device", C.c_int32)]
+                ("block_n", C.c_int32), ("tau_rel", C.c_float), ("tau_abs", C.c_float), ("fold_tokens", C.c_int32),
+                ("max_events", C.c_int32), ("device", C.c_int32)]
 
 
 class Fault(C.Structure):
@@ -98,9 +98,11 @@ class FtGemm:
     """One context of the C library: Y = X W^T for one (m, n, k) on one device."""
 
     def __init__(self, m: int, n: int, k: int, out_dtype: int = F32, ft_mode: int = FT_CORRECT, tau_rel: float = 0.0,
-                 tau_abs: float = -1.0, max_events: int = 0, device: int = 0, in_dtype: int = F16):
+                 tau_abs: float = -1.0, max_events: int = 0, device: int = 0, in_dtype: int = F16,
+                 fold_tokens: bool = False):
         self.lib = load_library()
-        cfg = Config(C.sizeof(Config), m, n, k, in_dtype, out_dtype, ft_mode, 8, 0, tau_rel, tau_abs, max_events, device)
+        cfg = Config(C.sizeof(Config), m, n, k, in_dtype, out_dtype, ft_mode, 8, 0, tau_rel, tau_abs, int(bool(fold_tokens)),
+                     max_events, device)
         self.handle = C.c_void_p()
         rc = self.lib.ftgemm_create(C.byref(cfg), C.byref(self.handle))
         if rc != OK:

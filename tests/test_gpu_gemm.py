@@ -179,3 +179,64 @@ def test_feed_forward_size_on_sampled_rows():
     assert rep.event_list() == sorted((int(rows[r]), c, a) for (r, c, a) in ev)
     assert np.all(np.abs(got[rows] - want) <= 2.0 ** -10 * np.maximum(1.0, np.abs(want)))
     assert rep.residual_max < 0.5
+
+
+# ---------------------------------------------------------------- checksums over the token rows (fold_tokens)
+
+def select_token_fold_faults(X, W, prm, n_faults, seed, bit_lo, bit_hi):
+    """One robust fault per output feature: with the checksums over the tokens, a feature column is
+    verified on its own, so the oracle's decision is taken on the one-feature problem."""
+    m, n = X.shape[0], W.shape[0]
+    accepted, cols = [], set()
+    for slot in range(n_faults):
+        stream = synth.linear_fault_stream(seed, slot, m, n, bit_lo, bit_hi)
+        for _ in range(200):
+            r, c, b = next(stream)
+            if c in cols:
+                continue
+            _, _, dg = orc.ftgemm(X, W[c:c + 1], prm, [(r, 0, b)])
+            if orc.fault_is_robust(dg) and not orc.fp32_is_fragile(dg["flipped"][0]):
+                accepted.append((r, c, b))
+                cols.add(c)
+                break
+        else:
+            raise RuntimeError(f"no robust fault for slot {slot}")
+    return np.asarray(accepted, np.int32)
+
+
+@pytest.mark.parametrize("m,n,k,dtype,out_dtype", [(512, 384, 128, synth.F16, ftgemm.F32), (300, 520, 128, synth.BF16, ftgemm.F32),
+                                                  (777, 515, 192, synth.F16, ftgemm.F16), (33, 9, 64, synth.F16, ftgemm.F32),
+                                                  (1, 1, 64, synth.BF16, ftgemm.BF16)])
+def test_token_fold_variant_matches_the_oracle(m, n, k, dtype, out_dtype):
+    print(f"[gemm token fold] m={m} n={n} k={k} dtype={dtype} out={out_dtype}", flush=True)
+    xb, wb = synth.gen_linear(m, n, k, synth.LINEAR_SEED_BASE + 6, dtype=dtype)
+    X, W = f64(xb, dtype), f64(wb, dtype)
+    prm = orc.Params(bf16=dtype == synth.BF16, fold_tokens=True)
+    ulp = {ftgemm.F32: 0.0, ftgemm.F16: 2.0 ** -10, ftgemm.BF16: 2.0 ** -7}[out_dtype]
+    tol = max(TOL32 if dtype == synth.F16 else 4e-3, ulp)
+    want = orc.linear_clean(X, W)
+    got, rep, cfg = run(xb, wb, ftgemm.FT_CORRECT, out_dtype=out_dtype, encode=False, dtype=dtype, fold_tokens=True)
+    assert cfg.fold_tokens == 1
+    assert np.all(np.abs(got - want) <= max(TOL32, ulp) * np.maximum(1.0, np.abs(want)))
+    assert rep.n_events == 0 and (m < 8 or 0.0 < rep.residual_max < 0.7)
+    if m * n < 64:
+        return
+    faults = select_token_fold_faults(X, W, prm, min(24, n), synth.LINEAR_SEED_BASE + 7, 0, 31)
+    cols = np.unique(faults[:, 1])
+    local = [(int(f[0]), int(np.searchsorted(cols, f[1])), int(f[2])) for f in faults]
+    for mode, correct in ((ftgemm.FT_CORRECT, True), (ftgemm.FT_DETECT, False)):
+        prm.correct = correct
+        want_f, ev, _ = orc.ftgemm(X, W[cols], prm, local)
+        got, rep, _ = run(xb, wb, mode, out_dtype=out_dtype, faults=faults, encode=False, dtype=dtype, fold_tokens=True)
+        assert rep.event_list() == sorted((r, int(cols[c]), a) for (r, c, a) in ev)
+        assert len(ev) > 0
+        g = got[:, cols]
+        if out_dtype == ftgemm.F16:
+            with np.errstate(over="ignore"):
+                want_f = np.where(np.abs(want_f) > 65520.0, np.sign(want_f) * np.inf, want_f)   # a damaged value left in place may exceed fp16
+        fin = np.isfinite(want_f)
+        assert np.array_equal(np.isfinite(g), fin)
+        assert np.all(np.abs(g[fin] - want_f[fin]) <= tol * np.maximum(1.0, np.abs(want_f[fin])))
+        # features without a fault are untouched
+        other = np.setdiff1d(np.arange(n), cols)
+        assert np.all(np.abs(got[:, other] - want[:, other]) <= max(TOL32, ulp) * np.maximum(1.0, np.abs(want[:, other])))

@@ -67,11 +67,11 @@ def test_create_rejects_bad_configs_without_a_device():
 
 def test_gemm_create_rejects_bad_configs_without_a_device():
     lib = ftgemm.load_library()
-    assert C.sizeof(ftgemm.Config) == 13 * 4 and C.sizeof(ftgemm.Fault) == 12
+    assert C.sizeof(ftgemm.Config) == 14 * 4 and C.sizeof(ftgemm.Fault) == 12
     assert C.sizeof(ftgemm.Event) == 16 == ftgemm.EVENT_DTYPE.itemsize
     def create(**kw):
         base = dict(struct_size=C.sizeof(ftgemm.Config), m=256, n=256, k=128, in_dtype=0, out_dtype=2, ft_mode=1,
-                    stride=8, block_n=0, tau_rel=0.0, tau_abs=-1.0, max_events=0, device=0)
+                    stride=8, block_n=0, tau_rel=0.0, tau_abs=-1.0, fold_tokens=0, max_events=0, device=0)
         base.update(kw)
         cfg = ftgemm.Config(**base)
         h = C.c_void_p()
@@ -86,6 +86,7 @@ def test_gemm_create_rejects_bad_configs_without_a_device():
     assert create(in_dtype=1, out_dtype=0)[0] == ftgemm.EINVAL
     assert create(stride=4)[0] == ftgemm.EUNSUPPORTED
     assert create(ft_mode=3)[0] == ftgemm.EINVAL
+    assert create(fold_tokens=2)[0] == ftgemm.EINVAL
     rc, msg = create(block_n=128)
     assert rc == ftgemm.EUNSUPPORTED and "block_n" in msg
     assert lib.ftgemm_forward(None, None, None, None, None, 0, None) == ftgemm.EINVAL
