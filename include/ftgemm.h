@@ -44,7 +44,7 @@ enum { FTGEMM_FT_OFF = 0, FTGEMM_FT_CORRECT = 1, FTGEMM_FT_DETECT = 2 };
 
 typedef struct {
   uint32_t struct_size;  /* sizeof(ftgemm_config), checked */
-  int32_t m, n, k;       /* m, n >= 1 (any value); k >= 64 and a multiple of 64 */
+  int32_t m, n, k;       /* m, n >= 1 (any value); k >= 8 and a multiple of 8 (rows are read in 16-byte chunks) */
   int32_t in_dtype;      /* FTGEMM_F16 | FTGEMM_BF16: type of x and w; the contraction runs on the MFMA of
                             that type with fp32 accumulation */
   int32_t out_dtype;     /* FTGEMM_F32, or the input type */

@@ -56,12 +56,14 @@ static void grelease(ftgemm_ctx* c) {
 
 typedef void (*gemm_fn)(const GArgs);
 
-template <bool BF> static gemm_fn select_gemm_t(bool ft, bool inject) {
-  if (ft) return inject ? ftgemm_main<true, true, BF> : ftgemm_main<true, false, BF>;
-  return inject ? ftgemm_main<false, true, BF> : ftgemm_main<false, false, BF>;
+template <bool BF, bool RAG> static gemm_fn select_gemm_t(bool ft, bool inject) {
+  if (ft) return inject ? ftgemm_main<true, true, BF, RAG> : ftgemm_main<true, false, BF, RAG>;
+  return inject ? ftgemm_main<false, true, BF, RAG> : ftgemm_main<false, false, BF, RAG>;
 }
-static gemm_fn select_gemm(bool ft, bool inject, bool bf) {
-  return bf ? select_gemm_t<true>(ft, inject) : select_gemm_t<false>(ft, inject);
+// ragged: k is not a multiple of the kernel's K step
+static gemm_fn select_gemm(bool ft, bool inject, bool bf, bool ragged) {
+  if (ragged) return bf ? select_gemm_t<true, true>(ft, inject) : select_gemm_t<false, true>(ft, inject);
+  return bf ? select_gemm_t<true, false>(ft, inject) : select_gemm_t<false, false>(ft, inject);
 }
 static size_t gemm_lds(bool ft) { return ft ? GStage<true>::LDS_TOTAL : GStage<false>::LDS_TOTAL; }
 
@@ -70,7 +72,7 @@ extern "C" int ftgemm_create(const ftgemm_config* cfg, ftgemm_ctx** out) {
   *out = nullptr;
   if (cfg->struct_size != sizeof(ftgemm_config)) return gfail(nullptr, FTGEMM_EINVAL, "struct_size mismatch");
   if (cfg->m < 1 || cfg->n < 1) return gfail(nullptr, FTGEMM_EINVAL, "m and n must be >= 1");
-  if (cfg->k < 64 || cfg->k % 64 != 0) return gfail(nullptr, FTGEMM_EUNSUPPORTED, "k must be a positive multiple of 64");
+  if (cfg->k < 8 || cfg->k % 8 != 0) return gfail(nullptr, FTGEMM_EUNSUPPORTED, "k must be a positive multiple of 8 (rows of 16-byte chunks)");
   if (cfg->in_dtype != FTGEMM_F16 && cfg->in_dtype != FTGEMM_BF16) return gfail(nullptr, FTGEMM_EINVAL, "in_dtype must be F16 or BF16");
   if (cfg->out_dtype != FTGEMM_F32 && cfg->out_dtype != cfg->in_dtype) return gfail(nullptr, FTGEMM_EINVAL, "out_dtype must be F32 or the input type");
   if (cfg->ft_mode < 0 || cfg->ft_mode > 2) return gfail(nullptr, FTGEMM_EINVAL, "ft_mode out of range");
@@ -120,7 +122,7 @@ extern "C" int ftgemm_create(const ftgemm_config* cfg, ftgemm_ctx** out) {
   GCREATE_TRY(hipMemset(c->d_ev_count, 0, sizeof(int32_t)));
   GCREATE_TRY(hipMemset(c->d_resmax, 0, sizeof(uint32_t)));
   for (int v = 0; v < 8; ++v)
-    GCREATE_TRY(hipFuncSetAttribute((const void*)select_gemm((v & 1) != 0, (v & 2) != 0, (v & 4) != 0),
+    GCREATE_TRY(hipFuncSetAttribute((const void*)select_gemm((v & 1) != 0, (v & 2) != 0, (v & 4) != 0, e.k % GBK != 0),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds((v & 1) != 0)));
   GCREATE_TRY(hipDeviceSynchronize());
 #undef GCREATE_TRY
@@ -196,7 +198,7 @@ extern "C" int ftgemm_forward(ftgemm_ctx* c, const void* x, const void* w, void*
   a.faults = c->d_faults; a.n_faults = n_faults;
   a.events = c->d_events; a.ev_count = c->d_ev_count; a.max_events = e.max_events;
   a.resmax = c->d_resmax;
-  gemm_fn f = select_gemm(ft, n_faults > 0, e.in_dtype == FTGEMM_BF16);
+  gemm_fn f = select_gemm(ft, n_faults > 0, e.in_dtype == FTGEMM_BF16, e.k % GBK != 0);
   if (c->timing) GHIP_TRY(c, hipEventRecord(c->ev[0], st));
   hipLaunchKernelGGL(f, dim3(c->Tm * c->Tn), dim3(GWAVES * 64), gemm_lds(ft), st, a);
   GHIP_TRY(c, hipGetLastError());

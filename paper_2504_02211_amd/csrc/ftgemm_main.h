@@ -139,7 +139,9 @@ __device__ __forceinline__ void log_gemm_event(const GArgs& a, int row, int col,
   }
 }
 
-template <bool FT, bool INJ, bool BF>
+// RAG: K is not a multiple of the K step (the last step is partly empty); a separate instantiation so that the
+// regular case carries none of its selects
+template <bool FT, bool INJ, bool BF, bool RAG = false>
 __global__ __launch_bounds__(GWAVES * 64) void ftgemm_main(const GArgs a) {
   using S = GStage<FT>;
   constexpr int NA = FT ? 9 : 8;          // A operands (32-row blocks of W, + the checksum block) per k-step
@@ -171,14 +173,17 @@ __global__ __launch_bounds__(GWAVES * 64) void ftgemm_main(const GArgs a) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int M = a.M, N = a.N, K = a.K;
   const int m0 = tm * GBM, n0 = tn * GBN;
-  const int nkb = K / GBK;
+  const int nkb = (K + GBK - 1) / GBK;
+  const int krem = K - (nkb - 1) * GBK;     // columns of the last K step (GBK unless K is ragged; K is a multiple of 8)
   const uint32_t smem_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
 
   // ---- per-lane source offsets of this wave's load instructions.  Instruction `ins` of a stage
   // fills LDS bytes [1024*ins, 1024*ins + 1024): 32 of them cover the token rows, 32 the weight
   // rows, 4 the checksum rows.  Rows beyond the matrix are clamped to its last row (their
-  // results are never used).
-  uint32_t off[S::NLOAD];
+  // results are never used).  In the last K step of a ragged K a chunk beyond column K is fetched
+  // from the first chunk of that step instead (valid memory); its products are switched off by
+  // zeroing the token operand of those columns below.
+  uint32_t off[S::NLOAD], offl[S::NLOAD];
 #pragma unroll
   for (int i = 0; i < S::NLOAD; ++i) {
     const int ins = wave + 8 * i;
@@ -190,6 +195,7 @@ __global__ __launch_bounds__(GWAVES * 64) void ftgemm_main(const GArgs a) {
     const int c = (L & 7) ^ ((r >> 1) & 7);
     if (r > rows_left - 1) r = rows_left - 1;
     off[i] = ((uint32_t)r * (uint32_t)K + (uint32_t)c * 8u) * 2u;
+    offl[i] = RAG ? ((uint32_t)r * (uint32_t)K + (c * 8 < krem ? (uint32_t)c * 8u : 0u)) * 2u : off[i];
   }
   const uint16_t* xb = a.x + (size_t)m0 * K;
   const uint16_t* wb = a.w + (size_t)n0 * K;
@@ -199,9 +205,10 @@ __global__ __launch_bounds__(GWAVES * 64) void ftgemm_main(const GArgs a) {
     const bool ok = real_piece && (i < 8 || wave < 4);
     const uint32_t dst = ok ? smem_base + (uint32_t)st * S::BYTES + (uint32_t)(wave + 8 * i) * 1024u : dump;
     const size_t koff = real_piece ? (size_t)kb * GBK : 0;
-    if (i < 4) gload_lds16_off(xb + koff, off[i], dst);
-    else if (i < 8) gload_lds16_off(wb + koff, off[i], dst);
-    else gload_lds16_off(cb + koff, off[i], dst);
+    const uint32_t o = RAG && kb >= nkb - 1 ? offl[i] : off[i];      // (the loads that go to the dump area stay inside the rows too)
+    if (i < 4) gload_lds16_off(xb + koff, o, dst);
+    else if (i < 8) gload_lds16_off(wb + koff, o, dst);
+    else gload_lds16_off(cb + koff, o, dst);
   };
 
   float16v acc[8], sc;
@@ -228,6 +235,12 @@ __global__ __launch_bounds__(GWAVES * 64) void ftgemm_main(const GArgs a) {
     half8 xf[NKS];
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks) xf[ks] = *reinterpret_cast<const half8*>(xst + (((2 * ks + hi) ^ swz) << 4));
+    if (RAG && kb == nkb - 1) {
+      // ragged K: the columns beyond K take no part (whatever the weight operand holds there)
+#pragma unroll
+      for (int ks = 0; ks < NKS; ++ks)
+        if ((2 * ks + hi) * 8 >= krem) xf[ks] = (half8)(_Float16)0.f;
+    }
     half8 buf[RING];
     auto load_op = [&](int k) __attribute__((always_inline)) -> half8 {
       const int ks = k / NA, y = k % NA;

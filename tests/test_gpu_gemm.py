@@ -46,7 +46,8 @@ def f64(bits, dtype=synth.F16):
     return synth.bits_to_f64(bits, dtype)
 
 
-SHAPES = [(256, 256, 64), (300, 520, 128), (515, 777, 192), (1024, 1024, 512), (33, 9, 64), (1, 1, 64)]
+SHAPES = [(256, 256, 64), (300, 520, 128), (515, 777, 192), (1024, 1024, 512), (33, 9, 64), (1, 1, 64),
+          (300, 520, 200), (64, 70, 8), (515, 333, 72)]          # the last three: K not a multiple of the 64-column step
 
 
 @pytest.mark.parametrize("m,n,k", SHAPES)
@@ -97,7 +98,8 @@ def select_faults(X, W, prm, n_faults, seed, bit_lo, bit_hi):
 
 @pytest.mark.parametrize("m,n,k,bits,dtype", [(512, 768, 256, (20, 30), synth.F16), (300, 520, 128, (0, 31), synth.F16),
                                               (515, 777, 192, (10, 31), synth.F16), (512, 768, 256, (18, 30), synth.BF16),
-                                              (300, 520, 2048, (0, 31), synth.BF16)])
+                                              (300, 520, 2048, (0, 31), synth.BF16), (300, 520, 200, (0, 31), synth.F16),
+                                              (257, 300, 1000, (10, 31), synth.BF16)])
 def test_injected_faults_are_detected_located_and_repaired_as_the_oracle_says(m, n, k, bits, dtype):
     print(f"[gemm faults] m={m} n={n} k={k} bits={bits} dtype={dtype}", flush=True)
     xb, wb = synth.gen_linear(m, n, k, synth.LINEAR_SEED_BASE + 2, dtype=dtype)

@@ -62,7 +62,7 @@ def test_random_linear_configurations():
     rng = np.random.default_rng(303)
     TT = {0: torch.float16, 1: torch.bfloat16, 2: torch.float32}
     for it in range(12):
-        m, n, k = int(rng.integers(1, 700)), int(rng.integers(1, 900)), 64 * int(rng.integers(1, 9))
+        m, n, k = int(rng.integers(1, 700)), int(rng.integers(1, 900)), 8 * int(rng.integers(1, 65))
         dt = int(rng.integers(0, 2))
         od = int(rng.choice([2, dt]))
         print(f"[random linear] m{m} n{n} k{k} dtype{dt} out{od}", flush=True)

@@ -79,7 +79,7 @@ def test_gemm_create_rejects_bad_configs_without_a_device():
         return rc, lib.ftgemm_last_error(None).decode()
     assert create(struct_size=8)[0] == ftgemm.EINVAL
     assert create(m=0)[0] == ftgemm.EINVAL
-    assert create(k=96)[0] == ftgemm.EUNSUPPORTED
+    assert create(k=100)[0] == ftgemm.EUNSUPPORTED
     assert create(k=0)[0] == ftgemm.EUNSUPPORTED
     assert create(in_dtype=2)[0] == ftgemm.EINVAL
     assert create(out_dtype=1)[0] == ftgemm.EINVAL          # bf16 out for fp16 in
