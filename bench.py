@@ -219,7 +219,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(the path shards over batch*heads and row tiles without communication, see DESIGN.md)", file=sys.stderr)
+              "(the path would shard over batch*heads and row tiles without communication)", file=sys.stderr)
         return 2
 
     if args.linear:
