@@ -19,10 +19,14 @@ A second mode (``--ber``) injects flips at a given rate per computed fp32 interm
 constraint on where they fall, and counts the rows that are wrong without protection, flagged
 under protection, and right again after correction.
 
+A third mode (``--linear``) does the threshold sweep for the strided ABFT of the linear layer
+(relative threshold tau_rel): one flip per output row, both checksum orientations.
+
 Everything here goes through the C ABI; the inputs are synthetic and seeded.
 
     python -m paper_2504_02211_amd.coverage --seq 2048 --heads 8 --faults-per-head 48
     python -m paper_2504_02211_amd.coverage --seq 2048 --heads 8 --ber 1e-7 1e-6 1e-5 1e-4
+    python -m paper_2504_02211_amd.coverage --linear [--fold-tokens]
 """
 from __future__ import annotations
 
@@ -31,7 +35,7 @@ from typing import Dict, List, Optional, Sequence, Tuple
 
 import numpy as np
 
-from . import ftattn, synth
+from . import ftattn, ftgemm, synth
 
 HARM_TOL = 2e-3
 FAMILIES = ("product", "sum", "range")
@@ -266,6 +270,72 @@ def to_markdown(res: Dict[str, object]) -> str:
     return "\n".join(out)
 
 
+
+LINEAR_GRID = tuple(2.0 ** e for e in (-21, -19, -17, -16, -15, -14, -13, -11, -9, -7))
+LINEAR_HARM = 1e-3          # a flip is harmful when it moves its output by more than this (outputs are of order one)
+
+
+def linear_sweep(m: int, n: int, k: int, dtype: int, n_faults: int, seed: int, fold_tokens: bool = False,
+                 grid: Sequence[float] = LINEAR_GRID) -> Dict[str, object]:
+    """Threshold sweep of the linear layer's check: for every tau_rel, how many of the harmful and of the
+    harmless flips (one per output row and column, bits 0..31) are flagged, how many of the harmful ones
+    are back within tolerance, and how many events a fault-free run raises."""
+    import torch
+    xb, wb = synth.gen_linear(m, n, k, seed, dtype=dtype)
+    tt = torch.float16 if dtype == synth.F16 else torch.bfloat16
+    x = torch.from_numpy(xb.view(np.int16)).cuda().view(tt)
+    w = torch.from_numpy(wb.view(np.int16)).cuda().view(tt)
+    rows, cols, faults = set(), set(), []
+    for slot in range(n_faults):
+        stream = synth.linear_fault_stream(seed + 1, slot, m, n, 0, 31)
+        for _ in range(1000):
+            r, c, b = next(stream)
+            if r not in rows and c not in cols:
+                rows.add(r); cols.add(c); faults.append((r, c, b))
+                break
+    fa = np.asarray(faults, np.int32)
+
+    def run(ft_mode, flt, tau_rel=0.0):
+        ctx = ftgemm.FtGemm(m, n, k, out_dtype=ftgemm.F32, ft_mode=ft_mode, tau_rel=tau_rel, in_dtype=dtype,
+                            fold_tokens=fold_tokens, max_events=1 << 20)
+        y = torch.empty((m, n), dtype=torch.float32, device="cuda")
+        if ft_mode != ftgemm.FT_OFF:
+            ctx.encode_weights(w)
+        ctx.forward(x, w, y, flt)
+        rep = ctx.report()
+        out = y.cpu().numpy()
+        ctx.close()
+        return out, rep
+
+    clean, _ = run(ftgemm.FT_OFF, None)
+    damaged, _ = run(ftgemm.FT_OFF, fa)
+    with np.errstate(all="ignore"):
+        dmg = np.abs(damaged[fa[:, 0], fa[:, 1]] - clean[fa[:, 0], fa[:, 1]])
+    harmful = ~(dmg <= LINEAR_HARM)                       # non-finite counts as harmful
+    curve = []
+    for tau in grid:
+        _, rep0 = run(ftgemm.FT_CORRECT, None, tau)
+        fixed, rep = run(ftgemm.FT_CORRECT, fa, tau)
+        ev = {(int(e["row"]), int(e["col"])) for e in rep.events}
+        hit = np.array([(int(f[0]), int(f[1])) in ev for f in fa])
+        with np.errstate(all="ignore"):
+            left = np.abs(fixed[fa[:, 0], fa[:, 1]] - clean[fa[:, 0], fa[:, 1]])
+        curve.append({"tau_rel": float(tau), "harmful": int(harmful.sum()), "harmful_detected": int((harmful & hit).sum()),
+                      "harmful_repaired": int((harmful & (left <= LINEAR_HARM)).sum()),
+                      "benign": int((~harmful).sum()), "benign_detected": int((~harmful & hit).sum()),
+                      "false_alarms": int(rep0.n_events), "residual_max": float(rep0.residual_max),
+                      "checks": int(m) * 8 * ((n + 255) // 256) if not fold_tokens else int(n) * 8 * ((m + 255) // 256)})
+    return {"m": m, "n": n, "k": k, "faults": int(len(fa)), "curve": curve}
+
+
+def linear_markdown(res: Dict[str, object]) -> str:
+    out = ["| tau_rel | harmful flips flagged | ... repaired | harmless flips flagged | events on a fault-free run (of checks) | largest fault-free residual / threshold |",
+           "|---|---|---|---|---|---|"]
+    for c in res["curve"]:
+        out.append(f"| 2^{int(np.log2(c['tau_rel']))} | {c['harmful_detected']}/{c['harmful']} | {c['harmful_repaired']}/{c['harmful']} | "
+                   f"{c['benign_detected']}/{c['benign']} | {c['false_alarms']} of {c['checks']} | {c['residual_max']:.3g} |")
+    return "\n".join(out)
+
 def main() -> None:
     ap = argparse.ArgumentParser(description=__doc__.split("\n")[0])
     ap.add_argument("--batch", type=int, default=2)
@@ -281,10 +351,19 @@ def main() -> None:
     ap.add_argument("--per-step", type=int, choices=(0, 1, 2), default=0,
                     help="bit-error-rate sweep: 1 = verification after every step, 2 = the same with the softmax "
                          "protected by duplication (0 = unified verification)")
+    ap.add_argument("--linear", action="store_true", help="threshold sweep of the linear layer's check instead of attention")
+    ap.add_argument("--fold-tokens", action="store_true", help="--linear: checksums over the token rows")
     ap.add_argument("--ber", type=float, nargs="*", default=None,
                     help="run the bit-error-rate sweep at these rates instead of the threshold sweep")
     args = ap.parse_args()
     dtype = synth.F16 if args.dtype == "fp16" else synth.BF16
+    if args.linear:
+        res = linear_sweep(2048, 2048, 1024, dtype, 512, args.seed, args.fold_tokens)
+        print(f"workload: linear layer 2048 tokens, 1024 -> 2048 features, {args.dtype}, X ~ N(0,1), W ~ N(0,1/k), seed {args.seed:#x}; "
+              f"{res['faults']} flips of bits 0..31, one per output row and column; checksums over the "
+              f"{'token' if args.fold_tokens else 'weight'} rows; harmful = moves its output by more than {LINEAR_HARM}")
+        print(linear_markdown(res))
+        return
     shape = (args.batch, args.heads, args.seq, args.head_dim)
     q, k, v = synth.gen_qkv(shape, dtype, args.seed)
     if args.ber is not None:

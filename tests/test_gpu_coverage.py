@@ -90,3 +90,20 @@ def test_bit_error_rate_sweep():
         mine = {e for e in got if e[0] == b and e[1] == h and e[4] == row}
         assert mine == {(b, h) + e for e in ev}, (fl, sorted(mine), ev)
     assert compared >= 5, compared
+
+
+def test_linear_layer_threshold_sweep():
+    """Shape of the coverage curve of the linear layer's check: at the default threshold every
+    harmful flip is flagged and repaired and a fault-free run raises nothing; detection can only
+    fall as the threshold grows; a threshold below the rounding noise of the two-word checksums
+    fires on clean data."""
+    res = coverage.linear_sweep(512, 768, 256, synth.BF16, 96, 0xC0FE, grid=(2.0 ** -24, 2.0 ** -15, 2.0 ** -11, 2.0 ** -7))
+    c = {r["tau_rel"]: r for r in res["curve"]}
+    d = c[2.0 ** -15]
+    assert d["harmful"] > 20 and d["harmful_detected"] == d["harmful"] == d["harmful_repaired"] and d["false_alarms"] == 0
+    det = [r["harmful_detected"] for r in res["curve"]]
+    assert all(a >= b for a, b in zip(det, det[1:])) and det[-1] < det[0]
+    assert c[2.0 ** -24]["false_alarms"] > 0
+    print(coverage.linear_markdown(res))
+    tok = coverage.linear_sweep(512, 768, 256, synth.F16, 96, 0xC0FE, fold_tokens=True, grid=(2.0 ** -15,))["curve"][0]
+    assert tok["harmful_detected"] == tok["harmful"] == tok["harmful_repaired"] and tok["false_alarms"] == 0
