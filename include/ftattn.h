@@ -72,8 +72,9 @@ typedef struct {
                              FTATTN_FT_CORRECT: detect, locate, correct;
                              FTATTN_FT_DETECT: detect and locate, leave values as they are */
   int32_t stride;         /* checksum stride s of eq. (13); 0 or 8 */
-  int32_t block_m, block_n; /* 0 selects the library's tile sizes; others are rejected unless
-                             supported.  Effective values: ftattn_get_config. */
+  int32_t block_m, block_n; /* 0 selects the library's tile sizes (256 queries x 64 keys for
+                             head_dim 128, 128 x 64 for head_dim 64); other values are
+                             rejected.  Effective values: ftattn_get_config. */
   float eps1;             /* threshold of the per-iteration product-form check on
                              |ln prod P - ln P^c1| (Algorithm 1, first "if"); <= 0 selects 0.03 */
   float tau_o;            /* threshold of the final sum-form check on the normalised output

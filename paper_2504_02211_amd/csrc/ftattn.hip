@@ -102,7 +102,8 @@ extern "C" int ftattn_create(const ftattn_config* cfg, ftattn_ctx** out) {
   if (cfg->ft_mode < 0 || cfg->ft_mode > 2) return fail(nullptr, FTATTN_EINVAL, "ft_mode out of range");
   if (cfg->stride != 0 && cfg->stride != 8) return fail(nullptr, FTATTN_EUNSUPPORTED, "stride must be 8");
   if (cfg->block_n != 0 && cfg->block_n != BN) return fail(nullptr, FTATTN_EUNSUPPORTED, "block_n must be 64");
-  if (cfg->block_m != 0 && cfg->block_m != BM) return fail(nullptr, FTATTN_EUNSUPPORTED, "block_m must be 256");
+  if (cfg->block_m != 0 && cfg->block_m != bm_of(cfg->head_dim))
+    return fail(nullptr, FTATTN_EUNSUPPORTED, "block_m must be 0 or the library's row tile (256 for head_dim 128, 128 for head_dim 64)");
   if (cfg->causal != 0 && cfg->causal != 1) return fail(nullptr, FTATTN_EINVAL, "causal must be 0 or 1");
   if (cfg->rowsum_fold != 0 && cfg->rowsum_fold != 1) return fail(nullptr, FTATTN_EINVAL, "rowsum_fold must be 0 or 1");
   if (cfg->per_step < 0 || cfg->per_step > 2) return fail(nullptr, FTATTN_EINVAL, "per_step must be 0, 1 or 2");
@@ -122,8 +123,8 @@ extern "C" int ftattn_create(const ftattn_config* cfg, ftattn_ctx** out) {
   if (e.max_events <= 0) e.max_events = 65536;
   c->BH = e.batch * e.heads;
   c->Tj = (e.seq + BN - 1) / BN;
-  e.block_m = BM;
-  c->BM = BM;
+  e.block_m = bm_of(e.head_dim);
+  c->BM = e.block_m;
   c->Ti = (e.seq + c->BM - 1) / c->BM;
 
   hipError_t he = hipSetDevice(e.device);
@@ -264,7 +265,7 @@ extern "C" int ftattn_forward(ftattn_ctx* c, const void* q, const void* k, const
   a.resmax = c->d_resmax; a.recheck = c->d_recheck;
   main_fn f = e.per_step ? select_perstep(D, e.causal != 0, n_faults > 0, e.per_step) : select_kernel(D, ft, e.causal != 0, n_faults > 0);
   if (c->timing) HIP_TRY(c, hipEventRecord(c->ev[1], st));
-  hipLaunchKernelGGL(f, dim3(c->BH * c->Ti), dim3(NWAVE * 64), lds_bytes(D, ft), st, a);
+  hipLaunchKernelGGL(f, dim3(c->BH * c->Ti), dim3(nwave_of(D) * 64), lds_bytes(D, ft), st, a);
   HIP_TRY(c, hipGetLastError());
   if (c->timing) HIP_TRY(c, hipEventRecord(c->ev[2], st));
   c->last_stream = st;

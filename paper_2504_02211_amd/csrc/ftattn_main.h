@@ -1,13 +1,19 @@
 // The fused fault-tolerant attention kernel (gfx950 / CDNA4): Algorithm 1 of the paper from
-// GEMM I to the final store, for one (batch, head, 256-query row tile) per workgroup.
+// GEMM I to the final store, for one (batch, head, query row tile) per workgroup.
 //
-// Execution shape.  Eight waves of 64 lanes; wave w owns queries 32w .. 32w+31 of the row tile.
-// The waves form two groups of four (one wave of each group per SIMD) that run half an iteration
-// apart: while one group is in its MATRIX phase (GEMM II of key tile i and GEMM I of key tile
-// i+1, back to back on the MFMA pipe) the other is in its SOFTMAX phase (max, exp, product-form
-// check, row-sum, rescale: vector ALU only), and at every workgroup barrier they trade places.
-// Key / value tiles arrive in LDS by direct global-to-LDS loads into a ring of three stages;
-// stage u holds V_u^T and K_{u+1}, the two operands one matrix phase reads.
+// Execution shape.  Wave w of a workgroup owns queries 32w .. 32w+31 of the row tile.
+//  * head_dim 128: eight waves (256-query row tiles), one workgroup per CU.  The waves form two
+//    groups of four (one wave of each group per SIMD) that run half an iteration apart: while one
+//    group is in its MATRIX phase (GEMM II of key tile i and GEMM I of key tile i+1, back to back
+//    on the MFMA pipe) the other is in its SOFTMAX phase (max, exp, product-form check, row-sum,
+//    rescale: vector ALU only), and at every workgroup barrier they trade places.  Key / value
+//    tiles arrive in LDS by direct global-to-LDS loads into a ring of three stages.
+//  * head_dim 64: four waves (128-query row tiles), two independent workgroups per CU, so that a
+//    SIMD again holds two waves, which the hardware interleaves as it finds them; one barrier per
+//    iteration, a ring of two stages.  With the smaller head the softmax phase is about twice the
+//    matrix phase, and the strict alternation would leave the matrix pipe and one of the two waves
+//    idle half of the time; free-running waves keep the vector ALU busy from both.
+// In either shape stage u of the ring holds V_u^T and K_{u+1}, the two operands one matrix phase reads.
 //
 // Register layout: see ftattn_device.h (scores transposed, one query per lane, the four
 // stride-8 checksum classes of a lane and all their folds in the lane's own registers).
@@ -16,9 +22,10 @@
 
 namespace ftattn {
 
-constexpr int NWAVE = 8;
-constexpr int BM = NWAVE * 32;
-constexpr int NSTAGE = 3;
+// waves per workgroup, query rows per workgroup and ring stages, by head_dim (see above)
+constexpr int nwave_of(int d) { return d == 64 ? 4 : 8; }
+constexpr int bm_of(int d) { return nwave_of(d) * 32; }
+constexpr int nstage_of(int d) { return nwave_of(d) == 8 ? 3 : 2; }
 
 template <int D, bool FT> struct Unit {
   static constexpr int KROWS = FT ? BN + CKR : BN;
@@ -28,6 +35,7 @@ template <int D, bool FT> struct Unit {
   static constexpr int BYTES = KBYTES + VBYTES;
   static constexpr int K_INSTR = KBYTES / 1024;     // one instruction moves 64 lanes x 16 bytes
   static constexpr int V_INSTR = VBYTES / 1024;
+  static constexpr int NWAVE = nwave_of(D), NSTAGE = nstage_of(D);
   static constexpr int KPW = (K_INSTR + NWAVE - 1) / NWAVE;
   static constexpr int VPW = (V_INSTR + NWAVE - 1) / NWAVE;
   // Every wave issues NLOAD instructions per unit; a wave that has no real piece left (uneven
@@ -35,9 +43,10 @@ template <int D, bool FT> struct Unit {
   // so that the counted waits below hold for every wave in every iteration.
   static constexpr int NLOAD = KPW + VPW;
   static constexpr int DUMP = 1024;
-  static constexpr int LDS_TOTAL = 3 * BYTES + DUMP;
+  static constexpr int LDS_TOTAL = NSTAGE * BYTES + DUMP;
   static_assert(K_INSTR >= NWAVE && V_INSTR >= NWAVE, "every wave owns at least one piece of each tile");
-  static_assert(2 * NLOAD <= 15, "counted waits use a 4-bit immediate");
+  static_assert((NSTAGE - 1) * NLOAD <= 15, "counted waits use a 4-bit immediate");
+  static_assert(NWAVE == 8 || 2 * LDS_TOTAL <= 160 * 1024, "two workgroups per CU");
 };
 
 // 16 bytes per lane from (uniform base + per-lane byte offset) straight into LDS at
@@ -70,10 +79,12 @@ __device__ __forceinline__ half2v opaque(half2v x) { asm volatile("" : "+v"(x));
 // product-form check and the range restriction: maximum, exponentials and reduce-sum are
 // evaluated twice and compared bit by bit; a third evaluation settles a difference.
 template <int D, bool FT, bool CAUSAL, bool INJ, int PS = 0>
-__global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
+__global__ __launch_bounds__(nwave_of(D) * 64, nwave_of(D) == 8 ? 1 : 2) void ftattn_main(const KArgs a) {
   static_assert(FT || PS == 0, "per-step verification is a mode of the protected kernel");
   constexpr bool DMR = PS == 2;
   using U = Unit<D, FT>;
+  constexpr int NWAVE = U::NWAVE, BM = NWAVE * 32, NSTAGE = U::NSTAGE;
+  constexpr bool ALT = NWAVE == 8;      // two wave groups alternating between the phases (else: free-running waves)
   constexpr int NSLAB = D / 16;     // k-slabs of GEMM I
   constexpr int NFB = D / 32;       // 32-feature blocks of O^T
   constexpr int NFOLD_V = D / 8;
@@ -93,7 +104,7 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
   const int ti = CAUSAL ? a.Ti - 1 - (logical % a.Ti) : (logical % a.Ti);   // heavy row tiles first
   const int tid = threadIdx.x, lane = tid & 63, lq = lane & 31, hi = lane >> 5;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int grp = wave >> 2;
+  const int grp = ALT ? wave >> 2 : 0;
   const int N = a.N;
   const int row0_cta = ti * BM;
   const int row0_w = row0_cta + wave * 32;
@@ -123,7 +134,7 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
     const int rv = L / 8, cv = (L % 8) ^ swz_v(rv);
     voff0 = (uint32_t)(rv * BN + cv * 8) * 2u;
   }
-  constexpr int PIECE_STEP = 4096;      // halfs between the sources of consecutive pieces of a wave
+  constexpr int PIECE_STEP = NWAVE * 64 * 8;      // halfs between the sources of consecutive pieces of a wave
   static_assert((NWAVE * 64 / KCH) * D == PIECE_STEP && (NWAVE * 64 / 8) * BN == PIECE_STEP, "piece stride");
   // unit u = { V_u^T, K_{u+1} } goes to stage (u+1) mod 3.  A unit is fetched in NLOAD pieces per
   // wave; the pieces of one unit are spread over a matrix phase (see matrix_stream).
@@ -166,7 +177,7 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
 
   issue_unit(-1, true);
   issue_unit(0, true);
-  issue_unit(1, nj >= 2);
+  if (ALT) issue_unit(1, nj >= 2);
 
   // ---- Q_i^T as MFMA B operand: lane (query lq, half hi) holds Q[row][16*slab + 8*hi .. +7]
   // (bf16 queries are converted here: exact for magnitudes in the fp16 normal range)
@@ -364,12 +375,14 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
   };
 
   // ---- prologue: the first key tile's scores; group 1 starts one barrier later than group 0
-  wait_vmcnt<2 * U::NLOAD>();                     // unit -1 has landed
+  wait_vmcnt<(NSTAGE - 1) * U::NLOAD>();          // unit -1 has landed
   phase_barrier();
-  if (grp == 1) phase_barrier();
+  if (ALT && grp == 1) phase_barrier();
   if (nj_w > 0) matrix_stream(smem_base, smem_base, no{}, yes{}, no{});
-  if (grp == 1) wait_vmcnt<U::NLOAD>();           // unit 0
-  phase_barrier();
+  if (ALT) {
+    if (grp == 1) wait_vmcnt<U::NLOAD>();         // unit 0
+    phase_barrier();
+  }
 
   for (int i = 0; i < nj; ++i) {
     const int k0 = i * BN;
@@ -662,11 +675,15 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
         if (FT) oc *= al;
       }
     }
-    if (grp == 0) wait_vmcnt<U::NLOAD>();         // unit i (unit i+1 may still be in flight)
-    phase_barrier();
+    if (ALT) {
+      if (grp == 0) wait_vmcnt<U::NLOAD>();       // unit i (unit i+1 may still be in flight)
+    } else {
+      wait_vmcnt<0>();                            // unit i (nothing younger has been requested)
+    }
+    phase_barrier();                              // ... everyone's pieces; and everyone is past the reads of the stage refilled next
 
     // =========================================================== matrix phase
-    prepare_unit(i + 2, i + 2 < nj);
+    prepare_unit(ALT ? i + 2 : i + 1, (ALT ? i + 2 : i + 1) < nj);
     __builtin_amdgcn_s_setprio(1);
     // (after a wave's last key tile GEMM I runs on a tile it does not need: same code, result unused)
     if (DMR) l_prev = l_part;
@@ -751,10 +768,12 @@ __global__ __launch_bounds__(NWAVE * 64) void ftattn_main(const KArgs a) {
       }
       if (sum_check(a.tau_o * l, i, real, false, 0.f, false)) wait_vmcnt<0>();
     }
-    if (grp == 1) wait_vmcnt<U::NLOAD>();         // unit i+1 (unit i+2 may still be in flight)
-    phase_barrier();
+    if (ALT) {
+      if (grp == 1) wait_vmcnt<U::NLOAD>();       // unit i+1 (unit i+2 may still be in flight)
+      phase_barrier();
+    }
   }
-  if (grp == 0) phase_barrier();
+  if (ALT && grp == 0) phase_barrier();
 
   // ================= after the loop: row-sum range check, normalisation, sum-form check, store
   float rmax_u = 0.f, rmax_l = 0.f;

@@ -30,14 +30,14 @@ def test_ragged_shapes(N, d, dtype, causal):
     assert ma <= 2e-3 and rf <= 1e-3, (ma, rf)
 
 
-@pytest.mark.parametrize("block_m", [0, 256])
-def test_row_tile_sizes_and_output_types(block_m):
-    N, d = 640, 128
+@pytest.mark.parametrize("d,block_m", [(128, 0), (128, 256), (64, 0), (64, 128)])
+def test_row_tile_sizes_and_output_types(d, block_m):
+    N = 640
     q, k, v = synth.gen_qkv((1, 2, N, d), synth.BF16, 77)
     prm = H.oracle_params(N, d, True)
     ref = _clean_all(q, k, v, synth.BF16, prm)
     out, rep, c = H.run_gpu(q, k, v, synth.BF16, True, block_m=block_m)
-    assert c.block_m == 256 and rep.n_events == 0
+    assert c.block_m == (256 if d == 128 else 128) and rep.n_events == 0      # the row tile goes with the head size
     ma, rf = H.tolerance_ok(out, ref)
     assert ma <= 2e-3 and rf <= 1e-3
     out16, _, _ = H.run_gpu(q, k, v, synth.BF16, True, block_m=block_m, out_dtype=synth.BF16)

@@ -60,6 +60,7 @@ def test_create_rejects_bad_configs_without_a_device():
     assert create(per_step=1, rowsum_fold=1)[0] == ftattn.EINVAL
     rc, msg = create(block_m=96)
     assert rc == ftattn.EUNSUPPORTED and "block_m" in msg
+    assert create(block_m=256)[0] == ftattn.EUNSUPPORTED       # head_dim 64 runs 128-query row tiles
     assert lib.ftattn_forward(None, None, None, None, None, None, 0, None) == ftattn.EINVAL
     assert lib.ftattn_report(None, None) == ftattn.EINVAL
     assert lib.ftattn_destroy(None) == ftattn.EINVAL
