@@ -177,6 +177,44 @@ def test_strided_multi_error_rows():
     assert np.abs(O[9] - clean[9]).max() > 1e-6                            # ... but not repaired
 
 
+
+def test_element_wide_checksum_versus_stride_8():
+    """The traditional checksum (one class over the whole tile row: stride 1) against the stride-8
+    tensor checksum (Section 3.3, and the coverage comparison of Section 4.2): without faults both
+    are silent and exact, one error per (row, key tile) is repaired by both, and of several errors
+    in one (row, key tile) the stride-8 fold repairs every one that has its class to itself while
+    the single class notices them and repairs none."""
+    Q, K, V = _rand(64, 16, 8)
+    clean = attention_clean(Q, K, V, 0.25, False)
+    wide = Params(scale=0.25, causal=False, block_n=32, stride=1)
+    tensor = Params(scale=0.25, causal=False, block_n=32, stride=8)
+    rows = np.arange(64)
+    for prm in (wide, tensor):
+        O, ev, _ = efta_rows(Q, rows, K, V, prm, [])
+        assert ev == [] and np.abs(O - clean).max() < 1e-12
+        one = [(ST_S, 1, 5, 41, 28)]
+        O, ev, _ = efta_rows(Q, rows, K, V, prm, one)
+        assert ev == [(CHECK_S, 1, 5, 41)] and np.abs(O - clean).max() < 1e-11
+        one = [(ST_OACC, 1, 7, 11, 27)]
+        O, ev, _ = efta_rows(Q, rows, K, V, prm, one)
+        assert [e[0] for e in ev] == [CHECK_O] and ev[0][3] == 11 and np.abs(O - clean).max() < 1e-11
+    rng = np.random.default_rng(77)
+    repaired = {1: 0, 8: 0}
+    noticed = {1: 0, 8: 0}
+    trials = 40
+    for t in range(trials):
+        row, tile = int(rng.integers(0, 64)), int(rng.integers(0, 2))
+        c0, c1 = rng.choice(8, size=2, replace=False)                      # two different classes
+        cols = [32 * tile + int(c0) + 8 * int(rng.integers(0, 4)), 32 * tile + int(c1) + 8 * int(rng.integers(0, 4))]
+        faults = [(ST_S, tile, row, cols[0], 28), (ST_S, tile, row, cols[1], 29)]
+        for prm in (wide, tensor):
+            O, ev, _ = efta_rows(Q, rows, K, V, prm, faults)
+            noticed[prm.stride] += len(ev) >= 1
+            repaired[prm.stride] += np.abs(O - clean).max() < 2e-3     # the parity tolerance: harmless residue counts as repaired
+    assert noticed[8] == trials and noticed[1] >= trials - 2      # (two errors may offset each other in one sum)
+    assert repaired[8] == trials and repaired[1] <= trials // 4, (noticed, repaired)
+
+
 # ---------------------------------------------------------------- softmax protection
 
 def test_case1_max_error_cancels():
