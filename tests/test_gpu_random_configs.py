@@ -15,7 +15,7 @@ import ft_harness as H
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("seed", [101, 202])
+@pytest.mark.parametrize("seed", [101, 202, 303, 404, 505, 606])
 def test_random_attention_configurations(seed):
     rng = np.random.default_rng(seed)
     for it in range(30):
