@@ -39,10 +39,10 @@ def measured_traffic(cfg: int):
     return None
 
 
-def time_variant(torch, ftattn, w, tq, tk, tv, ft_mode, steps, warmup, block_m, rowsum_fold=False, per_step=0):
+def time_variant(torch, ftattn, w, tq, tk, tv, ft_mode, steps, warmup, block_m, rowsum_fold=False, per_step=0, stride=8):
     o = torch.empty((w.batch, w.heads, w.seq, w.head_dim), dtype=torch.float32, device="cuda")
     ctx = ftattn.FtAttn(w.batch, w.heads, w.seq, w.head_dim, w.dtype, w.causal, ft_mode=ft_mode, block_m=block_m,
-                        rowsum_fold=rowsum_fold, per_step=per_step)
+                        rowsum_fold=rowsum_fold, per_step=per_step, stride=stride)
     stream = torch.cuda.Stream()
     sp = stream.cuda_stream
     for _ in range(warmup):
@@ -209,6 +209,9 @@ def main():
     ap.add_argument("--per-step", type=int, choices=(0, 1, 2), default=0,
                     help="attention: 1 = verification after every step (the paper's EFTA before unified verification), "
                          "2 = the same with the softmax protected by duplication; 0 = unified (default)")
+    ap.add_argument("--stride", type=int, choices=(8, 1), default=8,
+                    help="attention: checksum stride; 1 = the traditional checksum (one class per tile row) the paper "
+                         "compares its stride-8 tensor checksum with")
     ap.add_argument("--linear", action="store_true",
                     help="time the protected feed-forward GEMM instead of attention (its own JSON line)")
     ap.add_argument("--linear-dtype", choices=("fp16", "bf16"), default="fp16")
@@ -240,7 +243,7 @@ def main():
         w = synth.WORKLOADS[cfg]
         q, k, v = synth.gen_workload(cfg)
         tq, tk, tv = (to_dev(x, w.dtype) for x in (q, k, v))
-        ft = time_variant(torch, ftattn, w, tq, tk, tv, ftattn.FT_CORRECT, args.steps, args.warmup, args.block_m, args.rowsum_fold, args.per_step)
+        ft = time_variant(torch, ftattn, w, tq, tk, tv, ftattn.FT_CORRECT, args.steps, args.warmup, args.block_m, args.rowsum_fold, args.per_step, args.stride)
         un = time_variant(torch, ftattn, w, tq, tk, tv, ftattn.FT_OFF, args.steps, args.warmup, args.block_m)
         results[cfg] = (w, ft, un)
         if cfg == args.workload:
@@ -260,7 +263,7 @@ def main():
         "dtype": "f16", "data": "synthetic",
         "config": {"workload": f"cfg{w.cfg} {w.name}: batch {w.batch}, heads {w.heads}, seq {w.seq}, head_dim {w.head_dim}, "
                                f"{'bf16' if w.dtype else 'fp16'} in, fp32 out, {'causal' if w.causal else 'non-causal'}, fault-free",
-                   "block_m": ft["block_m"], "block_n": ft["block_n"], "stride": 8,
+                   "block_m": ft["block_m"], "block_n": ft["block_n"], "stride": args.stride,
                    "rowsum_protection": "extra checksum fold" if args.rowsum_fold else "range restriction",
                    "verification": ("unified", "after every step", "after every step, duplicated softmax")[args.per_step]},
         "unprotected_tflops": round(tf_un, 2), "unprotected_ms_per_step": round(un["ms_step"], 4),

@@ -71,7 +71,13 @@ typedef struct {
   int32_t ft_mode;        /* FTATTN_FT_OFF: same kernel with every check compiled out;
                              FTATTN_FT_CORRECT: detect, locate, correct;
                              FTATTN_FT_DETECT: detect and locate, leave values as they are */
-  int32_t stride;         /* checksum stride s of eq. (13); 0 or 8 */
+  int32_t stride;         /* checksum stride s of eq. (13): 0 or 8 = the strided tensor checksum (eight
+                             classes per tile row); 1 = the traditional checksum the paper compares
+                             it with (Sections 3.3, 4.2): one class over the 64 keys of a tile row and
+                             one over all features, formed from the same encoded tiles, so that a row
+                             has one residual per key tile and can name one element of it.  Needs a
+                             protected ft_mode, rowsum_fold 0 and per_step 0.  Other values are
+                             rejected */
   int32_t block_m, block_n; /* 0 selects the library's tile sizes (256 queries x 64 keys for
                              head_dim 128, 128 x 64 for head_dim 64); other values are
                              rejected.  Effective values: ftattn_get_config. */

@@ -78,11 +78,12 @@ class Runner:
     """Keeps the operands on the device and runs one forward call per threshold setting."""
 
     def __init__(self, q: np.ndarray, k: np.ndarray, v: np.ndarray, dtype: int, causal: bool, rowsum_fold: bool = False,
-                 per_step: int = 0):
+                 per_step: int = 0, stride: int = 8):
         import torch
         self.torch = torch
         self.rowsum_fold = rowsum_fold
         self.per_step = per_step
+        self.stride = stride
         self.shape = q.shape
         self.dtype, self.causal = dtype, causal
         self.tq, self.tk, self.tv = (_to_torch(x, dtype) for x in (q, k, v))
@@ -92,7 +93,8 @@ class Runner:
         B, H, N, d = self.shape
         ctx = ftattn.FtAttn(B, H, N, d, self.dtype, self.causal, ft_mode=ft_mode, max_events=1 << 20,
                             rowsum_fold=self.rowsum_fold,
-                            per_step=self.per_step if ft_mode == ftattn.FT_CORRECT else 0, **thresholds)
+                            per_step=self.per_step if ft_mode == ftattn.FT_CORRECT else 0,
+                            stride=self.stride if ft_mode != ftattn.FT_OFF else 8, **thresholds)
         o = torch.empty((B, H, N, d), dtype=torch.float32, device="cuda")
         ctx.forward(self.tq, self.tk, self.tv, o, faults, torch.cuda.current_stream().cuda_stream)
         rep = ctx.report()
@@ -194,11 +196,11 @@ def draw_ber_faults(batch: int, heads: int, seq: int, head_dim: int, causal: boo
 
 
 def ber_sweep(q: np.ndarray, k: np.ndarray, v: np.ndarray, dtype: int, causal: bool, bers: Sequence[float],
-              seed: int, rowsum_fold: bool = False, per_step: int = 0) -> List[Dict[str, object]]:
+              seed: int, rowsum_fold: bool = False, per_step: int = 0, stride: int = 8) -> List[Dict[str, object]]:
     """For every bit error rate: how many rows the flips damage when nothing protects them, how
     many of those rows raise an event under protection, and how many are back within the
     tolerance after correction (default thresholds)."""
-    r = Runner(q, k, v, dtype, causal, rowsum_fold, per_step)
+    r = Runner(q, k, v, dtype, causal, rowsum_fold, per_step, stride)
     B, H, N, d = q.shape
     clean, _, cfg = r.run(None, ftattn.FT_OFF)
     rows_out = []
@@ -351,6 +353,9 @@ def main() -> None:
     ap.add_argument("--per-step", type=int, choices=(0, 1, 2), default=0,
                     help="bit-error-rate sweep: 1 = verification after every step, 2 = the same with the softmax "
                          "protected by duplication (0 = unified verification)")
+    ap.add_argument("--stride", type=int, choices=(8, 1), default=8,
+                    help="bit-error-rate sweep: 1 = the traditional checksum (one class per tile row) instead of the "
+                         "stride-8 tensor checksum")
     ap.add_argument("--linear", action="store_true", help="threshold sweep of the linear layer's check instead of attention")
     ap.add_argument("--fold-tokens", action="store_true", help="--linear: checksums over the token rows")
     ap.add_argument("--ber", type=float, nargs="*", default=None,
@@ -372,8 +377,10 @@ def main() -> None:
               f"{'non-causal' if args.non_causal else 'causal'}, N(0,1) inputs, seed {args.seed:#x}; "
               f"{population(*shape, not args.non_causal, 64)} fp32 intermediates per pass; row-sum protection: "
               f"{'extra checksum fold' if args.rowsum_fold else 'range restriction'}; verification: "
-              f"{('unified', 'after every step', 'after every step, duplicated softmax')[args.per_step]}")
-        print(ber_markdown(ber_sweep(q, k, v, dtype, not args.non_causal, bers, args.seed + 2, args.rowsum_fold, args.per_step)))
+              f"{('unified', 'after every step', 'after every step, duplicated softmax')[args.per_step]}; checksum: "
+              f"{'stride 8 (tensor checksum)' if args.stride == 8 else 'stride 1 (traditional, one class per tile row)'}")
+        print(ber_markdown(ber_sweep(q, k, v, dtype, not args.non_causal, bers, args.seed + 2, args.rowsum_fold, args.per_step,
+                                     args.stride)))
         return
     faults = draw_faults(*shape, not args.non_causal, 64, args.faults_per_head, args.seed + 1)
     res = sweep(q, k, v, dtype, not args.non_causal, faults)

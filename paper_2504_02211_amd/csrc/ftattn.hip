@@ -77,7 +77,10 @@ static main_fn pick(bool ft, bool causal) {
 // inject: the variant that carries the fault-injection code; calls without a fault list run the
 // variant that has none of it
 // the per-step instantiations live in a translation unit of their own (ftattn_perstep.hip)
-namespace ftattn { void (*select_perstep(int D, bool causal, bool inject, int mode))(const KArgs); }
+namespace ftattn {
+void (*select_perstep(int D, bool causal, bool inject, int mode))(const KArgs);
+void (*select_elementwide(int D, bool causal, bool inject))(const KArgs);
+}
 
 static main_fn select_kernel(int D, bool ft, bool causal, bool inject) {
   if (D == 128) return inject ? pick<128, true>(ft, causal) : pick<128, false>(ft, causal);
@@ -100,7 +103,7 @@ extern "C" int ftattn_create(const ftattn_config* cfg, ftattn_ctx** out) {
   if (cfg->in_dtype != FTATTN_F16 && cfg->in_dtype != FTATTN_BF16) return fail(nullptr, FTATTN_EINVAL, "in_dtype must be F16 or BF16");
   if (cfg->out_dtype != FTATTN_F32 && cfg->out_dtype != cfg->in_dtype) return fail(nullptr, FTATTN_EINVAL, "out_dtype must be F32 or the input type");
   if (cfg->ft_mode < 0 || cfg->ft_mode > 2) return fail(nullptr, FTATTN_EINVAL, "ft_mode out of range");
-  if (cfg->stride != 0 && cfg->stride != 8) return fail(nullptr, FTATTN_EUNSUPPORTED, "stride must be 8");
+  if (cfg->stride != 0 && cfg->stride != 8 && cfg->stride != 1) return fail(nullptr, FTATTN_EUNSUPPORTED, "stride must be 8 (or 1: the traditional checksum)");
   if (cfg->block_n != 0 && cfg->block_n != BN) return fail(nullptr, FTATTN_EUNSUPPORTED, "block_n must be 64");
   if (cfg->block_m != 0 && cfg->block_m != bm_of(cfg->head_dim))
     return fail(nullptr, FTATTN_EUNSUPPORTED, "block_m must be 0 or the library's row tile (256 for head_dim 128, 128 for head_dim 64)");
@@ -109,12 +112,14 @@ extern "C" int ftattn_create(const ftattn_config* cfg, ftattn_ctx** out) {
   if (cfg->per_step < 0 || cfg->per_step > 2) return fail(nullptr, FTATTN_EINVAL, "per_step must be 0, 1 or 2");
   if (cfg->per_step != 0 && (cfg->ft_mode != FTATTN_FT_CORRECT || cfg->rowsum_fold != 0))
     return fail(nullptr, FTATTN_EINVAL, "per_step needs ft_mode FTATTN_FT_CORRECT and rowsum_fold 0");
+  if (cfg->stride == 1 && (cfg->ft_mode == FTATTN_FT_OFF || cfg->rowsum_fold != 0 || cfg->per_step != 0))
+    return fail(nullptr, FTATTN_EINVAL, "stride 1 needs a protected ft_mode, rowsum_fold 0 and per_step 0");
 
   ftattn_ctx* c = new (std::nothrow) ftattn_ctx();
   if (!c) return fail(nullptr, FTATTN_ENOMEM, "out of host memory");
   c->cfg = *cfg;
   ftattn_config& e = c->cfg;
-  e.stride = 8;
+  e.stride = cfg->stride == 1 ? 1 : 8;
   e.block_n = BN;
   if (!(e.softmax_scale > 0.f)) e.softmax_scale = 1.0f / std::sqrt((float)e.head_dim);
   if (!(e.eps1 > 0.f)) e.eps1 = 0.03f;
@@ -169,6 +174,12 @@ extern "C" int ftattn_create(const ftattn_config* cfg, ftattn_ctx** out) {
   if (e.per_step)
     for (int v = 0; v < 4; ++v) {
       main_fn f = select_perstep(D, (v & 1) != 0, (v >> 1) != 0, e.per_step);
+      if (!f) { release(c); return fail(nullptr, FTATTN_EUNSUPPORTED, "no kernel for this tile shape"); }
+      CREATE_TRY(hipFuncSetAttribute((const void*)f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes(D, true)));
+    }
+  if (e.stride == 1)
+    for (int v = 0; v < 4; ++v) {
+      main_fn f = select_elementwide(D, (v & 1) != 0, (v >> 1) != 0);
       if (!f) { release(c); return fail(nullptr, FTATTN_EUNSUPPORTED, "no kernel for this tile shape"); }
       CREATE_TRY(hipFuncSetAttribute((const void*)f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes(D, true)));
     }
@@ -263,7 +274,9 @@ extern "C" int ftattn_forward(ftattn_ctx* c, const void* q, const void* k, const
   a.fault_off = n_faults > 0 ? c->d_fault_off : nullptr;
   a.events = c->d_events; a.ev_count = c->d_ev_count; a.max_events = e.max_events;
   a.resmax = c->d_resmax; a.recheck = c->d_recheck;
-  main_fn f = e.per_step ? select_perstep(D, e.causal != 0, n_faults > 0, e.per_step) : select_kernel(D, ft, e.causal != 0, n_faults > 0);
+  main_fn f = e.per_step ? select_perstep(D, e.causal != 0, n_faults > 0, e.per_step)
+              : e.stride == 1 ? select_elementwide(D, e.causal != 0, n_faults > 0)
+                              : select_kernel(D, ft, e.causal != 0, n_faults > 0);
   if (c->timing) HIP_TRY(c, hipEventRecord(c->ev[1], st));
   hipLaunchKernelGGL(f, dim3(c->BH * c->Ti), dim3(nwave_of(D) * 64), lds_bytes(D, ft), st, a);
   HIP_TRY(c, hipGetLastError());

@@ -78,10 +78,18 @@ __device__ __forceinline__ half2v opaque(half2v x) { asm volatile("" : "+v"(x));
 // PS == 2: in addition the softmax is protected by duplication (eq. (11), (12)) instead of the
 // product-form check and the range restriction: maximum, exponentials and reduce-sum are
 // evaluated twice and compared bit by bit; a third evaluation settles a difference.
+// PS == 3: unified verification with the traditional checksum instead of the strided one (the
+// comparison of Section 3.3 / 4.2): one class over the whole tile row (64 keys) and one over all
+// features, i.e. stride 1 in eq. (13).  Its checksum values are the sums over the eight stride-8
+// classes of the same encoded tiles (c1 = sum_c c1_c, c2 = sum_c 8 c2_c + (c - 7) c1_c), so the
+// matrix work is the same; what changes is that a row has one residual per key tile, formed by
+// the two lanes of a query together, and can name one element of 64 (of D for the output).
 template <int D, bool FT, bool CAUSAL, bool INJ, int PS = 0>
 __global__ __launch_bounds__(nwave_of(D) * 64, nwave_of(D) == 8 ? 1 : 2) void ftattn_main(const KArgs a) {
-  static_assert(FT || PS == 0, "per-step verification is a mode of the protected kernel");
+  static_assert(FT || PS == 0, "the verification modes are modes of the protected kernel");
   constexpr bool DMR = PS == 2;
+  constexpr bool STEP = PS == 1 || PS == 2;
+  constexpr bool EW = PS == 3;
   using U = Unit<D, FT>;
   constexpr int NWAVE = U::NWAVE, BM = NWAVE * 32, NSTAGE = U::NSTAGE;
   constexpr bool ALT = NWAVE == 8;      // two wave groups alternating between the phases (else: free-running waves)
@@ -304,6 +312,73 @@ __global__ __launch_bounds__(nwave_of(D) * 64, nwave_of(D) == 8 ? 1 : 2) void ft
   // (-1 after the loop), `xfold` / `xv` the extra fold of class 0 in the exact row-sum mode.
   float rmax_o = 0.f;
   auto sum_check = [&](const float thr, const int tile, const bool real, const bool xf, const float xv, const bool track) -> bool {
+    if (EW) {
+      // one class over all D features of the row (fold index = feature), from both lanes of the query
+      float sum1 = 0.f, chk1 = 0.f;
+#pragma unroll
+      for (int fb = 0; fb < NFB; ++fb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sum1 += o[fb][v];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) chk1 += oc[r] + oc[4 + r];
+      sum1 = sum32(sum1); chk1 = sum32(chk1);
+      const float R1 = chk1 - sum1;
+      const bool d = real && !(__builtin_fabsf(R1) <= thr);
+      if (track && !d && real) rmax_o = fmax2(rmax_o, __builtin_fabsf(R1));
+      if (!wave_any(d)) return false;
+      float chk2 = 0.f, sum2 = 0.f, big = -1.f;
+      int l_big = -1;
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        chk2 += 8.0f * (oc[8 + r] + oc[12 + r]) + (float)(4 * hi + r - 7) * (oc[r] + oc[4 + r]);
+#pragma unroll
+      for (int fb = 0; fb < NFB; ++fb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int l = 32 * fb + 8 * (v >> 2) + 4 * hi + (v & 3);
+          const float ov = o[fb][v];
+          sum2 += (float)(l + 1) * ov;
+          const float mag = finitef(ov) ? __builtin_fabsf(ov) : __builtin_inff();
+          if (mag > big) { big = mag; l_big = l; } else if (mag == big) { l_big = -1; }
+        }
+      chk2 = sum32(chk2); sum2 = sum32(sum2);
+      {
+        const float bigp = xchg32(big, hi);
+        const int lp = (int)xchg32((float)l_big, hi);
+        if (bigp > big) l_big = lp; else if (bigp == big) l_big = -1;
+      }
+      int lstar = -1;
+      {
+        const float ratio = (chk2 - sum2) / R1;
+        if (finitef(ratio)) {
+          const float c = __builtin_rintf(ratio) - 1.0f;
+          if (c >= 0.f && c < (float)D) lstar = (int)c;
+        } else {
+          lstar = l_big;
+        }
+      }
+      if (!d) lstar = -1;
+      float rest = 0.f;
+#pragma unroll
+      for (int fb = 0; fb < NFB; ++fb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (32 * fb + 8 * (v >> 2) + 4 * hi + (v & 3) != lstar) rest += o[fb][v];
+      rest = sum32(rest);
+      if (d) {
+        const bool fix = a.correct && lstar >= 0;
+        if (hi == 0) log_event(a, bh, FTATTN_CHECK_O, tile, row, lstar, R1, fix ? 1 : 0);
+        if (fix) {
+          const float val = chk1 - rest;
+#pragma unroll
+          for (int fb = 0; fb < NFB; ++fb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+              if (32 * fb + 8 * (v >> 2) + 4 * hi + (v & 3) == lstar) o[fb][v] = val;
+        }
+      }
+      return true;       // events may have been written
+    }
     bool bad = false;
     float R[4];
 #pragma unroll
@@ -519,10 +594,13 @@ __global__ __launch_bounds__(nwave_of(D) * 64, nwave_of(D) == 8 ? 1 : 2) void ft
               float s2 = ex2(__builtin_fmaf(chk, c_chk, c_m));
               float pr = ((p[0][r] * p[0][4 + r]) * s2) * ((p[0][8 + r] * p[0][12 + r]) * s2);
               pr *= ((p[1][r] * p[1][4 + r]) * s2) * ((p[1][8 + r] * p[1][12 + r]) * s2);
-              dv[r] = pr - 1.0f;
-              bad |= !(__builtin_fabsf(dv[r]) <= a.tau_fast);
+              if (EW) dv[r] = pr;
+              else {
+                dv[r] = pr - 1.0f;
+                bad |= !(__builtin_fabsf(dv[r]) <= a.tau_fast);
+              }
             }
-            if (PS) {
+            if (STEP) {
               // strided ABFT of GEMM I alone (eq. (15)): same sum order as the exact evaluation below
               float sum1 = 0.f;
 #pragma unroll
@@ -532,9 +610,17 @@ __global__ __launch_bounds__(nwave_of(D) * 64, nwave_of(D) == 8 ? 1 : 2) void ft
               bad |= !(a.scale * __builtin_fabsf(chk - sum1) <= 0.5f * a.eps1);
             }
           }
+          if (EW) {
+            // one class per row: the product of all 64 exponentials, from both lanes of the query
+            const float pl = (dv[0] * dv[1]) * (dv[2] * dv[3]);
+            dv[0] = pl * xchg32(pl, hi) - 1.0f;
+            bad = !(__builtin_fabsf(dv[0]) <= a.tau_fast);
+          }
           recheck = wave_any(bad);
           if (recheck) ++rechecks;
-          else {
+          else if (EW) {
+            dev_max = fmax2(dev_max, __builtin_fabsf(dv[0]));
+          } else {
             // largest deviation that passed (two three-input maxima; the values are finite here)
             asm("v_max3_f32 %0, %0, |%1|, |%2|" : "+v"(dev_max) : "v"(dv[0]), "v"(dv[1]));
             asm("v_max3_f32 %0, %0, |%1|, |%2|" : "+v"(dev_max) : "v"(dv[2]), "v"(dv[3]));
@@ -544,8 +630,97 @@ __global__ __launch_bounds__(nwave_of(D) * 64, nwave_of(D) == 8 ? 1 : 2) void ft
           // ============ exact re-evaluation (rare: a fast check tripped, or the tile is masked).
           // lambda = ln prod P - (sigma*check1_eff - n_valid*m) = sum_l (ln P_l - x_l) - sigma*R1.
           bool lin_fixed = false, logged = false;
+          if (EW) {
+            // the whole tile row as one class (fold index = position of the key in the tile): every
+            // sum is the lane's half plus its partner's, formed by all lanes alike (the exchanges
+            // are wave-wide operations); only the event and the writes depend on the outcome
+            float sum1 = 0.f, sum2 = 0.f, E = 0.f, chk1 = 0.f, chk2 = 0.f, big = -1.f;
+            int nvalid = 0, l_big = -1;
 #pragma unroll
-          for (int r = 0; r < 4; ++r) {
+            for (int r = 0; r < 4; ++r) {
+              const float c1 = sc[r] + sc[4 + r];
+              chk1 += c1;
+              chk2 += 8.0f * (sc[8 + r] + sc[12 + r]) + (float)(4 * hi + r - 7) * c1;
+            }
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+              for (int v = 0; v < 16; ++v) {
+                const int l = key_of(kb, v, hi), key = k0 + l;
+                const bool ok = key < N && (!CAUSAL || key <= row);
+                const float sv = s[kb][v];
+                sum1 += sv;
+                sum2 += (float)(l + 1) * sv;
+                const float mag = finitef(sv) ? __builtin_fabsf(sv) : __builtin_inff();
+                if (mag > big) { big = mag; l_big = l; } else if (mag == big) { l_big = -1; }
+                const float t = __builtin_fmaf(sv, sl2, negm);
+                const float pe = ex2(t);
+                if (ok) {
+                  ++nvalid;
+                  if (as_u(pe) != as_u(p[kb][v])) E += lg2(p[kb][v]) - t;
+                }
+              }
+            sum1 = sum32(sum1); sum2 = sum32(sum2); E = sum32(E); chk1 = sum32(chk1); chk2 = sum32(chk2);
+            nvalid += (int)xchg32((float)nvalid, hi);
+            {
+              const float bigp = xchg32(big, hi);
+              const int lp = (int)xchg32((float)l_big, hi);
+              if (bigp > big) l_big = lp; else if (bigp == big) l_big = -1;
+            }
+            const float R1 = chk1 - sum1;
+            const float lam = LN2 * E - a.scale * R1;
+            const bool linear = !(a.scale * __builtin_fabsf(R1) <= 0.5f * a.eps1);
+            const bool det = nvalid > 0 && !(__builtin_fabsf(lam) <= a.eps1);
+            int lstar = -1;
+            {
+              const float ratio = (chk2 - sum2) / R1;
+              if (finitef(ratio)) {
+                const float c = __builtin_rintf(ratio) - 1.0f;
+                if (c >= 0.f && c < (float)BN) lstar = (int)c;
+              } else {
+                lstar = l_big;
+              }
+            }
+            if (!(det && linear)) lstar = -1;
+            float rest = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+              for (int v = 0; v < 16; ++v)
+                if (key_of(kb, v, hi) != lstar) rest += s[kb][v];
+            rest = sum32(rest);
+            if (det) {
+              logged = true;
+              if (linear) {
+                const bool fix = a.correct && lstar >= 0;
+                if (hi == 0) log_event(a, bh, FTATTN_CHECK_S, i, row, lstar >= 0 ? k0 + lstar : -1, lam, fix ? 1 : 0);
+                if (fix) {
+                  const float val = chk1 - rest;
+#pragma unroll
+                  for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                      if (key_of(kb, v, hi) == lstar) s[kb][v] = val;
+                  lin_fixed = true;
+                }
+              } else {
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                  for (int v = 0; v < 16; ++v) {
+                    const int key = k0 + key_of(kb, v, hi);
+                    const bool ok = key < N && (!CAUSAL || key <= row);
+                    const float pe = ex2(__builtin_fmaf(s[kb][v], sl2, negm));
+                    if (ok && as_u(pe) != as_u(p[kb][v])) {
+                      log_event(a, bh, FTATTN_CHECK_EXP, i, row, key, lam, a.correct ? 1 : 0);
+                      if (a.correct) p[kb][v] = pe;
+                    }
+                  }
+              }
+            }
+          }
+#pragma unroll
+          for (int r = 0; r < 4 && !EW; ++r) {
             float chk1 = sc[r] + sc[4 + r];
             float sum1 = 0.f, E = 0.f;
             int nvalid = 0;
@@ -568,7 +743,7 @@ __global__ __launch_bounds__(nwave_of(D) * 64, nwave_of(D) == 8 ? 1 : 2) void ft
             float R1 = chk1 - sum1;
             float lam = LN2 * E - a.scale * R1;
             const bool linear = !(a.scale * __builtin_fabsf(R1) <= 0.5f * a.eps1);
-            bool det = nvalid > 0 && (DMR ? (linear || differs) : (!(__builtin_fabsf(lam) <= a.eps1) || (PS && linear)));
+            bool det = nvalid > 0 && (DMR ? (linear || differs) : (!(__builtin_fabsf(lam) <= a.eps1) || (STEP && linear)));
             if (det) {
               logged = true;
               if (linear) {
@@ -723,7 +898,7 @@ __global__ __launch_bounds__(nwave_of(D) * 64, nwave_of(D) == 8 ? 1 : 2) void ft
       }
       while (fcur < fend && F[fcur].kv_tile == i) ++fcur;
     }
-    if (PS && on) {
+    if (STEP && on) {
       // ---- verification of this iteration's reduce-sum (range so far, Section 3.4 case 3) and of
       // GEMM II with the rescale (sum-form check on the unnormalised accumulator)
       const bool real = row < N;

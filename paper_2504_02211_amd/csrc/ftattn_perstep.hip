@@ -1,6 +1,7 @@
-// Instantiations of the fused attention kernel with verification after every step (the paper's
-// EFTA before the unified verification of Section 3.4; optionally with its duplicated softmax), kept apart from the main translation unit
-// so that the two compile side by side.
+// Instantiations of the fused attention kernel in its ablation modes: verification after every
+// step (the paper's EFTA before the unified verification of Section 3.4; optionally with its
+// duplicated softmax), kept apart from the main translation unit so that the two compile side by
+// side.  The traditional-checksum mode is in a third translation unit.
 #include "ftattn_main.h"
 
 namespace ftattn {

@@ -127,10 +127,10 @@ class FtAttn:
     def __init__(self, batch: int, heads: int, seq: int, head_dim: int, in_dtype: int, causal: bool,
                  out_dtype: int = F32, ft_mode: int = FT_CORRECT, softmax_scale: float = 0.0, block_m: int = 0,
                  eps1: float = 0.0, tau_o: float = 0.0, delta_l: float = 0.0, max_events: int = 0, device: int = 0,
-                 rowsum_fold: bool = False, per_step: int = 0):
+                 rowsum_fold: bool = False, per_step: int = 0, stride: int = 8):
         self.lib = load_library()
         cfg = Config(C.sizeof(Config), batch, heads, seq, head_dim, in_dtype, out_dtype, int(bool(causal)),
-                     softmax_scale, ft_mode, 8, block_m, 0, eps1, tau_o, delta_l, int(bool(rowsum_fold)), int(per_step), max_events, device)
+                     softmax_scale, ft_mode, int(stride), block_m, 0, eps1, tau_o, delta_l, int(bool(rowsum_fold)), int(per_step), max_events, device)
         self.handle = C.c_void_p()
         rc = self.lib.ftattn_create(C.byref(cfg), C.byref(self.handle))
         if rc != OK:

@@ -23,13 +23,14 @@ def test_random_attention_configurations(seed):
         d, dtype, causal = int(rng.choice([64, 128])), int(rng.integers(0, 2)), bool(rng.integers(0, 2))
         mode = int(rng.integers(0, 3))                       # 0 unified, 1 after every step, 2 + duplicated softmax
         fold = bool(rng.integers(0, 2)) and mode == 0
+        stride = 1 if mode == 0 and not fold and bool(rng.integers(0, 2)) else 8      # 1: the traditional checksum
         scale = float(rng.choice([1.0, 0.25, 2.0]))
-        tag = f"B{B} H{Hh} N{N} d{d} dtype{dtype} causal{causal} rowsum_fold{fold} per_step{mode} scale{scale}"
+        tag = f"B{B} H{Hh} N{N} d{d} dtype{dtype} causal{causal} rowsum_fold{fold} per_step{mode} stride{stride} scale{scale}"
         print(f"[random attention] {tag}", flush=True)
         q, k, v = synth.gen_qkv((B, Hh, N, d), dtype, 1000 * seed + it, value_scale=scale)
-        out, rep, c = H.run_gpu(q, k, v, dtype, causal, rowsum_fold=fold, per_step=mode)
+        out, rep, c = H.run_gpu(q, k, v, dtype, causal, rowsum_fold=fold, per_step=mode, stride=stride)
         prm = H.oracle_params(N, d, causal, block_n=c.block_n, scale=c.softmax_scale, eps1=c.eps1, tau_o=c.tau_o,
-                              delta_l=c.delta_l, rowsum_fold=fold, per_step=mode > 0, softmax_dmr=mode == 2)
+                              delta_l=c.delta_l, rowsum_fold=fold, per_step=mode > 0, softmax_dmr=mode == 2, stride=stride)
         assert rep.n_events == 0, (tag, rep.events[:4])
         rows = np.unique(rng.integers(0, N, size=min(N, 24)))
         for b in range(B):
@@ -44,7 +45,7 @@ def test_random_attention_configurations(seed):
             faults, _ = H.select_faults(slots, 5000 * seed + it, q, k, v, dtype, prm, int(rng.integers(0, 22)), 31)
         except RuntimeError:
             continue                                         # no fault of this draw is clear of every threshold
-        out2, rep2, _ = H.run_gpu(q, k, v, dtype, causal, faults, rowsum_fold=fold, per_step=mode)
+        out2, rep2, _ = H.run_gpu(q, k, v, dtype, causal, faults, rowsum_fold=fold, per_step=mode, stride=stride)
         expected, got, ref = set(), [], []
         for (b, h) in sorted({(int(f[0]), int(f[1])) for f in faults}):
             fr = np.array(sorted({int(f[4]) for f in faults if f[0] == b and f[1] == h}))

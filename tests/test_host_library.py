@@ -58,6 +58,10 @@ def test_create_rejects_bad_configs_without_a_device():
     assert create(per_step=2, ft_mode=2)[0] == ftattn.EINVAL
     assert create(per_step=1, ft_mode=2)[0] == ftattn.EINVAL       # per-step verification repairs as it goes
     assert create(per_step=1, rowsum_fold=1)[0] == ftattn.EINVAL
+    assert create(stride=4)[0] == ftattn.EUNSUPPORTED
+    assert create(stride=1, ft_mode=0)[0] == ftattn.EINVAL           # the traditional checksum is a mode of the protected kernel
+    assert create(stride=1, rowsum_fold=1)[0] == ftattn.EINVAL
+    assert create(stride=1, per_step=1)[0] == ftattn.EINVAL
     rc, msg = create(block_m=96)
     assert rc == ftattn.EUNSUPPORTED and "block_m" in msg
     assert create(block_m=256)[0] == ftattn.EUNSUPPORTED       # head_dim 64 runs 128-query row tiles
