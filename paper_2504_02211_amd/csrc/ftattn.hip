@@ -76,7 +76,8 @@ static main_fn pick(bool ft, bool causal) {
 
 // inject: the variant that carries the fault-injection code; calls without a fault list run the
 // variant that has none of it
-// the per-step instantiations live in a translation unit of their own (ftattn_perstep.hip)
+// the ablation modes are instantiated in translation units of their own (ftattn_perstep.hip,
+// ftattn_elementwide.hip), so that all of them compile side by side
 namespace ftattn {
 void (*select_perstep(int D, bool causal, bool inject, int mode))(const KArgs);
 void (*select_elementwide(int D, bool causal, bool inject))(const KArgs);
