@@ -246,19 +246,16 @@ extern "C" int ftattn_forward(ftattn_ctx* c, const void* q, const void* k, const
 
   const bool ft = e.ft_mode != FTATTN_FT_OFF;
   int n_resmax = c->BH * c->Ti * 4;
-  ftattn_reset<<<(n_resmax + 255) / 256, 256, 0, st>>>(c->d_ev_count, c->d_recheck, c->d_resmax, n_resmax);
-
   if (c->timing) HIP_TRY(c, hipEventRecord(c->ev[0], st));
-  // ---- encode (Algorithm 1: "Encode tensor checksum"), once per key tile for all row tiles
-  dim3 eg(c->Tj, c->BH);
+  // ---- encode (Algorithm 1: "Encode tensor checksum"), once per key tile for all row tiles; the same
+  // launch clears the counters of the report
+  dim3 eg(c->Tj, c->BH, 2);
   const int bf = e.in_dtype == FTATTN_BF16 ? 1 : 0;
-  if (D == 128) {
-    ftattn_encode_k<128><<<eg, 128, 0, st>>>(k, bf, c->kc, N, c->Tj, ft ? 1 : 0);
-    ftattn_encode_v<128><<<eg, 256, 0, st>>>(v, bf, c->vt, N, c->Tj, ft ? 1 + e.rowsum_fold : 0);
-  } else {
-    ftattn_encode_k<64><<<eg, 64, 0, st>>>(k, bf, c->kc, N, c->Tj, ft ? 1 : 0);
-    ftattn_encode_v<64><<<eg, 256, 0, st>>>(v, bf, c->vt, N, c->Tj, ft ? 1 + e.rowsum_fold : 0);
-  }
+  const int kchk = ft ? 1 : 0, vchk = ft ? 1 + e.rowsum_fold : 0;
+  if (D == 128)
+    ftattn_prepare<128><<<eg, 256, 0, st>>>(k, v, bf, c->kc, c->vt, N, c->Tj, kchk, vchk, c->d_ev_count, c->d_recheck, c->d_resmax, n_resmax);
+  else
+    ftattn_prepare<64><<<eg, 256, 0, st>>>(k, v, bf, c->kc, c->vt, N, c->Tj, kchk, vchk, c->d_ev_count, c->d_recheck, c->d_resmax, n_resmax);
 
   // ---- the fused pass
   KArgs a;

@@ -147,14 +147,14 @@ __device__ __forceinline__ half8 to_half8(uint4v raw, bool bf16) {
   return r;
 }
 
-// One workgroup per (key tile, head), one thread per (checksum class, 16-byte chunk of a row): the
-// thread converts the 8 rows of its class to fp16 and forms, in fp32 registers, the four checksum
-// words of check1[c,:] = sum_l K[c+8l,:] and check2[c,:] = sum_l (l+1) K[c+8l,:]  (eq. (13), (14)).
+// Key tile j of head bh by the first D threads of a workgroup, one thread per (checksum class,
+// 16-byte chunk of a row): the thread converts the 8 rows of its class to fp16 and forms, in fp32
+// registers, the four checksum words of check1[c,:] = sum_l K[c+8l,:] and
+// check2[c,:] = sum_l (l+1) K[c+8l,:]  (eq. (13), (14)).
 template <int D>
-__global__ __launch_bounds__(D) void ftattn_encode_k(const void* __restrict__ k, int bf16, _Float16* __restrict__ kc,
-                                                     int N, int Tj, int with_checksums) {
+__device__ __forceinline__ void encode_k_tile(const void* __restrict__ k, int bf16, _Float16* __restrict__ kc,
+                                              int N, int Tj, int with_checksums, int j, int bh, int tid) {
   constexpr int KCH = D / 8;
-  const int j = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x;
   const int cls = tid / KCH, ch = tid % KCH;
   const uint16_t* src = reinterpret_cast<const uint16_t*>(k) + (size_t)bh * N * D + ch * 8;
   _Float16* out = kc + ((size_t)bh * Tj + j) * ((BN + CKR) * D) + ch * 8;
@@ -199,18 +199,17 @@ __device__ __forceinline__ int vt_key(int p) {
   return 32 * kb + 16 * G + 8 * b + 4 * hi + r;
 }
 
-// One workgroup per (key tile, head): V^T in fp16 (16-byte loads, transposition through LDS,
-// 16-byte stores) followed by the checksum rows of
+// Value tile j of head bh by a whole workgroup of 256 threads: V^T in fp16 (16-byte loads,
+// transposition through LDS, 16-byte stores) followed by the checksum rows of
 // check1[key, c] = sum_l V[key, c+8l] and check2 with weights l+1.
 template <int D>
-__global__ __launch_bounds__(256) void ftattn_encode_v(const void* __restrict__ v, int bf16, _Float16* __restrict__ vt,
-                                                       int N, int Tj, int with_checksums) {
+__device__ __forceinline__ void encode_v_tile(const void* __restrict__ v, int bf16, _Float16* __restrict__ vt,
+                                              int N, int Tj, int with_checksums, int j, int bh, int tid) {
   // with_checksums == 2: class 0 also folds a column of ones at feature index D (fold D/8), which
   // makes the first checksum of class 0 carry the row-sum through GEMM II
   constexpr int KCH = D / 8, PITCH = D + 8;
   __shared__ __attribute__((aligned(16))) _Float16 tile[BN * PITCH];
   __shared__ __attribute__((aligned(16))) _Float16 cks[CKR * BN];
-  const int j = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x;
   const uint16_t* src = reinterpret_cast<const uint16_t*>(v) + (size_t)bh * N * D;
   _Float16* out = vt + ((size_t)bh * Tj + j) * ((D + CKR) * BN);
   for (int e = tid; e < BN * KCH; e += 256) {
@@ -249,12 +248,25 @@ __global__ __launch_bounds__(256) void ftattn_encode_v(const void* __restrict__ 
   *reinterpret_cast<half8*>(out + D * BN + tid * 8) = *reinterpret_cast<const half8*>(cks + tid * 8);
 }
 
-// clears the event counter, the recheck counter and the residual maxima (a fill kernel rather
-// than a memset so that a caller may capture the forward call in a graph)
-static __global__ void ftattn_reset(int32_t* ev_count, unsigned long long* recheck, uint32_t* resmax, int n_resmax) {
-  int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i == 0) { *ev_count = 0; *recheck = 0ull; }
-  if (i < n_resmax) resmax[i] = 0u;
+// Everything the fused pass needs before it starts, in one launch (Algorithm 1: "Encode tensor
+// checksum"): grid (key tiles, heads, 2); the workgroups with blockIdx.z == 0 encode the value tiles
+// and clear the event counter, the recheck counter and the residual maxima (a store per thread
+// rather than a memset, so that a caller may capture the forward call in a graph), those with
+// blockIdx.z == 1 encode the key tiles.
+template <int D>
+__global__ __launch_bounds__(256) void ftattn_prepare(const void* __restrict__ k, const void* __restrict__ v, int bf16,
+                                                      _Float16* __restrict__ kc, _Float16* __restrict__ vt, int N, int Tj,
+                                                      int k_checksums, int v_checksums, int32_t* ev_count,
+                                                      unsigned long long* recheck, uint32_t* resmax, int n_resmax) {
+  const int j = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x;
+  if (blockIdx.z == 0) {
+    const long long i = ((long long)bh * Tj + j) * 256 + tid;
+    if (i == 0) { *ev_count = 0; *recheck = 0ull; }
+    if (i < n_resmax) resmax[i] = 0u;
+    encode_v_tile<D>(v, bf16, vt, N, Tj, v_checksums, j, bh, tid);
+  } else if (tid < D) {
+    encode_k_tile<D>(k, bf16, kc, N, Tj, k_checksums, j, bh, tid);
+  }
 }
 
 }  // namespace ftattn
