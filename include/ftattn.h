@@ -161,7 +161,7 @@ int ftattn_forward(ftattn_ctx* ctx, const void* q, const void* k, const void* v,
 /* Waits for the last forward of this context and exposes its flags, residuals and events. */
 int ftattn_report(ftattn_ctx* ctx, ftattn_report_view* out);
 /* Kernel timing for benchmarks.  After ftattn_set_timing(ctx, 1) every forward brackets its
- * encode kernels and its fused kernel with HIP events on the stream it launches on;
+ * encode kernel and its fused kernel with HIP events on the stream it launches on;
  * ftattn_get_timing waits for the last forward and returns the two durations in milliseconds:
  * ms[0] = encode (Algorithm 1, "Encode tensor checksum", plus operand conversion / transposition),
  * ms[1] = fused attention kernel (all other steps of Algorithm 1). */
