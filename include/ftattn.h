@@ -31,6 +31,8 @@
  *   - The context owns all device scratch (encoded K / V tiles, fault and event buffers).
  *     ftattn_forward allocates nothing and is asynchronous on the stream it is given, except
  *     that a non-empty fault list is uploaded synchronously before the launch.
+ *     Without a fault list (and with timing off) the call is kernel launches only: no
+ *     allocation, memset or copy, so it may be recorded into a HIP graph by stream capture.
  *   - One context serves one shape; calls on one context must not overlap in time.
  */
 #ifndef FTATTN_H

@@ -24,6 +24,8 @@
  *   - The context owns the device scratch (the encoded checksum rows of W, fault and event
  *     buffers).  ftgemm_forward allocates nothing and is asynchronous on its stream, except
  *     that a non-empty fault list is uploaded synchronously before the launch.
+ *     Without a fault list the call is kernel launches only (no allocation, memset or copy),
+ *     so it may be recorded into a HIP graph by stream capture.
  *   - One context serves one shape; calls on one context must not overlap in time.
  */
 #ifndef FTGEMM_H

@@ -142,3 +142,40 @@ def test_error_paths():
     with pytest.raises(ftattn.FtAttnError):
         ctx.forward(t.data_ptr() + 2, t, t, o)         # misaligned pointer
     ctx.close()
+
+
+def test_forward_in_a_captured_graph():
+    """A fault-free forward call launches kernels only (no allocation, no memset, no copy), so a
+    caller may capture it in a HIP graph: several replays, with eager work and new inputs between
+    them, each equal bit for bit to the eager call on the same inputs."""
+    import torch
+    from paper_2504_02211_amd import ftattn
+    B, Hh, N, d = 2, 3, 700, 128
+    dtype = synth.BF16
+    ctx = ftattn.FtAttn(B, Hh, N, d, dtype, True)
+    inputs = [tuple(H.to_torch(x, dtype) for x in synth.gen_qkv((B, Hh, N, d), dtype, 0x6A0 + i)) for i in range(3)]
+    q, k, v = (t.clone() for t in inputs[0])
+    o = torch.empty((B, Hh, N, d), dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        ctx.forward(q, k, v, o, None, side.cuda_stream)          # warm-up on the capturing stream
+    side.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        ctx.forward(q, k, v, o, None, torch.cuda.current_stream().cuda_stream)
+    for rep in range(4):
+        src = inputs[rep % 3]
+        for dst, s_ in zip((q, k, v), src):
+            dst.copy_(s_)
+        o.fill_(float("nan"))
+        junk = (q.float() * 2).sum()                               # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = o.clone()
+        assert ctx.report().n_events == 0
+        ref = torch.empty_like(o)
+        ctx.forward(q, k, v, ref, None, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert torch.isfinite(junk) and torch.equal(got, ref), rep
+    ctx.close()

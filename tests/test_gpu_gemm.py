@@ -242,3 +242,42 @@ def test_token_fold_variant_matches_the_oracle(m, n, k, dtype, out_dtype):
         # features without a fault are untouched
         other = np.setdiff1d(np.arange(n), cols)
         assert np.all(np.abs(got[:, other] - want[:, other]) <= max(TOL32, ulp) * np.maximum(1.0, np.abs(want[:, other])))
+
+
+@pytest.mark.parametrize("fold_tokens", [False, True])
+def test_forward_in_a_captured_graph(fold_tokens):
+    """A fault-free forward call launches kernels only, so a caller may capture it in a HIP graph:
+    several replays, with eager work and new activations between them, each equal bit for bit to
+    the eager call on the same inputs (with checksums over the token rows the per-call encode is
+    part of the graph)."""
+    m, n, k = 515, 777, 192
+    ctx = ftgemm.FtGemm(m, n, k, out_dtype=ftgemm.F32, ft_mode=ftgemm.FT_CORRECT, in_dtype=synth.F16, fold_tokens=fold_tokens)
+    xs = []
+    for i in range(3):
+        xb, wb = synth.gen_linear(m, n, k, 0x6B0 + i)
+        xs.append(dev16(xb))
+    w = dev16(wb)
+    x = xs[0].clone()
+    y = torch.empty((m, n), dtype=torch.float32, device="cuda")
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        ctx.encode_weights(w, side.cuda_stream)
+        ctx.forward(x, w, y, None, side.cuda_stream)            # warm-up on the capturing stream
+    side.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        ctx.forward(x, w, y, None, torch.cuda.current_stream().cuda_stream)
+    for rep in range(4):
+        x.copy_(xs[rep % 3])
+        y.fill_(float("nan"))
+        junk = (x.float() * 2).sum()                             # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = y.clone()
+        assert ctx.report().n_events == 0
+        ref = torch.empty_like(y)
+        ctx.forward(x, w, ref, None, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        assert torch.isfinite(junk) and torch.equal(got, ref), rep
+    ctx.close()
