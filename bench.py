@@ -273,7 +273,7 @@ def main():
         "ms_fused_kernel_unprotected": round(un["ms_main"], 4),
         "fast_path_rechecks": ft["rechecks"], "events": ft["events"],
         "roofline": {"bound": "mfma", "achieved": round(tf_kernel, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(tf_kernel / MFMA_PEAK_TFLOPS, 4), "traffic": measured_traffic(w.cfg),
+                     "frac": round(tf_kernel / MFMA_PEAK_TFLOPS, 4), "traffic": measured_traffic(w.cfg) if not (args.rowsum_fold or args.per_step or args.stride != 8) else None,
                      "kernel": "ftattn_main (fused FT attention)", "algorithmic_flops_per_launch": fl},
     }
     if args.all_workloads:
