@@ -179,3 +179,30 @@ def test_forward_in_a_captured_graph():
         torch.cuda.synchronize()
         assert torch.isfinite(junk) and torch.equal(got, ref), rep
     ctx.close()
+
+
+def test_long_ragged_sequence_on_sampled_rows():
+    """A sequence longer than any workload of the paper's evaluation, not a multiple of either tile
+    size (626 key tiles, the last with one key): sampled rows against the oracle, and one fault
+    late in the sequence located where the oracle says."""
+    B, Hh, N, d = 1, 2, 40001, 128
+    dtype = synth.BF16
+    q, k, v = synth.gen_qkv((B, Hh, N, d), dtype, 0x10A6)
+    out, rep, c = H.run_gpu(q, k, v, dtype, True)
+    assert rep.n_events == 0
+    prm = H.oracle_params(N, d, True, block_n=c.block_n, scale=c.softmax_scale, eps1=c.eps1, tau_o=c.tau_o, delta_l=c.delta_l)
+    rows = np.array([0, 63, 64, 255, 256, 12345, 39935, 39936, 39999, 40000])
+    for h in range(Hh):
+        clean, _, ev = H.oracle_rows(q, k, v, dtype, prm, 0, h, rows, np.zeros((0, 7), np.int32))
+        ma, rf = H.tolerance_ok(out[0, h][rows], clean)
+        assert ev == set() and ma <= 2e-3 and rf <= 1e-3, (h, ma, rf)
+    slots = [(0, h, 0, (synth.ST_S,)) for h in range(Hh)] + [(0, h, 1, (synth.ST_OACC,)) for h in range(Hh)]
+    faults, _ = H.select_faults(slots, 0x10A7, q, k, v, dtype, prm, 24, 30)
+    out2, rep2, _ = H.run_gpu(q, k, v, dtype, True, faults)
+    expected = set()
+    for (b, h) in sorted({(int(f[0]), int(f[1])) for f in faults}):
+        fr = np.array(sorted({int(f[4]) for f in faults if f[0] == b and f[1] == h}))
+        _, oft, ev = H.oracle_rows(q, k, v, dtype, prm, b, h, fr, faults)
+        expected |= ev
+        assert np.abs(out2[b, h][fr] - oft).max() <= 2e-3
+    assert rep2.event_set() == expected and len(expected) >= 2
