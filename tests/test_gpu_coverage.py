@@ -56,14 +56,15 @@ def test_sweep_shape_and_oracle_agreement():
         assert compared >= 24, compared
 
 
-def test_bit_error_rate_sweep():
-    """Unconstrained flips at two rates: no event on a row that no flip hit; at the low rate (flips on
+@pytest.mark.parametrize("stride", [8, 1])
+def test_bit_error_rate_sweep(stride):
+    """(stride 1: the traditional single-class checksum.)  Unconstrained flips at two rates: no event on a row that no flip hit; at the low rate (flips on
     separate rows) every row that is still wrong after correction carries a row-sum flip (the range
     restriction is the weak check), and the events of every hit row equal the oracle's."""
     shape = (1, 2, 640, 64)
     dtype, causal = synth.F16, True
     q, k, v = synth.gen_qkv(shape, dtype, 0xC0FE)
-    rows = coverage.ber_sweep(q, k, v, dtype, causal, (2e-5, 1e-3), 0xBE7)
+    rows = coverage.ber_sweep(q, k, v, dtype, causal, (2e-5, 1e-3), 0xBE7, stride=stride)
     print(coverage.ber_markdown(rows), flush=True)
     lo, hi = rows
     assert lo["faults"] >= 8 and hi["faults"] > 20 * lo["faults"]
@@ -74,10 +75,11 @@ def test_bit_error_rate_sweep():
     assert lo["rows_bad_after"] == st["ROWSUM"]
 
     faults = coverage.draw_ber_faults(*shape, causal, 64, 2e-5, 0xBE7)
-    r = coverage.Runner(q, k, v, dtype, causal)
+    r = coverage.Runner(q, k, v, dtype, causal, stride=stride)
     _, rep, cfg = r.run(faults, ftattn.FT_CORRECT)
+    assert cfg.stride == stride
     prm = H.oracle_params(shape[2], shape[3], causal, block_n=cfg.block_n, scale=cfg.softmax_scale,
-                          eps1=cfg.eps1, tau_o=cfg.tau_o, delta_l=cfg.delta_l)
+                          eps1=cfg.eps1, tau_o=cfg.tau_o, delta_l=cfg.delta_l, stride=stride)
     got = rep.event_set()
     compared = 0
     for (b, h, row) in sorted({(int(f[0]), int(f[1]), int(f[4])) for f in faults}):
