@@ -206,3 +206,33 @@ def test_long_ragged_sequence_on_sampled_rows():
         expected |= ev
         assert np.abs(out2[b, h][fr] - oft).max() <= 2e-3
     assert rep2.event_set() == expected and len(expected) >= 2
+
+
+def test_two_contexts_on_two_streams():
+    """Contexts own their scratch: two of them (different shapes) run on two streams at the same
+    time and give what they give one after the other."""
+    import torch
+    from paper_2504_02211_amd import ftattn
+    specs = [((1, 4, 1500, 128), synth.BF16, True), ((2, 3, 900, 64), synth.F16, False)]
+    ctxs, tens, refs = [], [], []
+    for i, (shape, dtype, causal) in enumerate(specs):
+        q, k, v = (H.to_torch(x, dtype) for x in synth.gen_qkv(shape, dtype, 0x2C0 + i))
+        ctx = ftattn.FtAttn(*shape, dtype, causal)
+        o = torch.empty(shape, dtype=torch.float32, device="cuda")
+        ctx.forward(q, k, v, o, None, torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        ctxs.append(ctx); tens.append((q, k, v)); refs.append(o.clone())
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = [torch.empty_like(r) for r in refs]
+    torch.cuda.synchronize()
+    for rep in range(5):
+        for o in outs:
+            o.fill_(float("nan"))
+        torch.cuda.synchronize()
+        for ctx, (q, k, v), o, st in zip(ctxs, tens, outs, streams):
+            ctx.forward(q, k, v, o, None, st.cuda_stream)
+        torch.cuda.synchronize()
+        for ctx, o, r in zip(ctxs, outs, refs):
+            assert torch.equal(o, r) and ctx.report().n_events == 0, rep
+    for ctx in ctxs:
+        ctx.close()
