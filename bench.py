@@ -186,7 +186,7 @@ def bench_linear(args):
         except Exception:
             cores = os.cpu_count() or 1
         t0 = time.perf_counter()
-        orc.ftgemm(X, W, orc.Params(bf16=dt == synth.BF16))
+        orc.ftgemm(X, W, orc.Params())
         secs = time.perf_counter() - t0
         out["cpu_baseline"] = {"value": round(2.0 * rows * n * k / secs / 1e12, 5), "unit": "TFLOP/s", "cores": int(cores),
                                "kind": "oracle", "sample": f"the first {rows} token rows of the same workload through the "

@@ -520,11 +520,19 @@ def fault_is_robust(diag: Dict[str, float], band: float = 4.0, l_band: float = 2
     return diag["l_distance"] > l_band and diag.get("l_step_distance", np.inf) > l_band
 
 
-def fp32_is_fragile(x: float, stage: int) -> bool:
-    """True when the fp32 value x sits so close to a power of two (or to zero, or to
-    the bottom of the normal range) that an fp32 evaluation of the same quantity in
-    another summation order could land in the neighbouring binade, which would
-    change what a flipped exponent or mantissa bit does to it."""
+def fp32_is_fragile(x: float, stage: int, bit: Optional[int] = None) -> bool:
+    """True when what a flipped bit does to the fp32 value x depends on rounding, i.e. when an
+    fp32 evaluation of the same quantity in another summation order (or from operands rounded to
+    16 bits first) could see another outcome of the same flip:
+
+    * x sits so close to a power of two (or to zero, or to the bottom of the normal range) that
+      the other evaluation could land in the neighbouring binade;
+    * (row-sum, with ``bit`` given) the flipped mantissa bit could have the other present value.
+      A flip of mantissa bit b adds 2^(b-23) 2^e when the bit is clear and subtracts it when set;
+      a row-sum formed from exponentials rounded to 16 bits differs from the exact one by up to
+      about 2^-9 of its size, so the bit is uncertain when x lies that close to a multiple of
+      2^(b-23) 2^e.  Bits below 10 move the row-sum by less than 2^-13 of its size in either
+      direction and are harmless whatever their value."""
     if not np.isfinite(x) or x == 0.0:
         return True
     ax = abs(float(x))
@@ -535,4 +543,10 @@ def fp32_is_fragile(x: float, stage: int) -> bool:
     if stage == ST_S:
         return gap < 2.0 ** -11                # raw scores: absolute accumulation noise
     rel = 2.0 ** -14 if stage == ST_EXP else 2.0 ** -9
-    return gap < rel * ax
+    if gap < rel * ax:
+        return True
+    if stage == ST_ROWSUM and bit is not None and 10 <= bit <= 22:
+        step = 2.0 ** (bit - 23) * 2.0 ** (ex - 1)      # weight of mantissa bit `bit` in x
+        off = ax % step
+        return min(off, step - off) < rel * ax
+    return False

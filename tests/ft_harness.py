@@ -23,9 +23,11 @@ def oracle_params(seq: int, head_dim: int, causal: bool, block_n: int = 64, scal
 def select_faults(slots, seed: int, q, k, v, dtype: int, prm: orc.Params, bit_lo: int, bit_hi: int,
                   max_attempts: int = 200) -> Tuple[np.ndarray, int]:
     """Draws one fault per slot from the seeded candidate streams, skipping candidates whose
-    detection would hinge on rounding (oracle statistics within 4x of a threshold), that sit on
-    a binade edge, that break the one-fault-per-cycle rule, or that share a row with an accepted
-    fault.  Returns (int32 [n,7] fault array, number of skipped candidates)."""
+    detection would hinge on rounding (oracle statistics within 4x of a threshold), whose flipped
+    value sits on a binade edge or (row-sum) has an uncertain value of the flipped mantissa bit, that
+    break the one-fault-per-cycle rule, or that share a row with an accepted fault.  Returns (int32
+    [n,7] fault array, number of skipped candidates); callers bound the skipped share with
+    ``assert_skip_share``."""
     B, H, N, d = q.shape
     accepted: List[Tuple[int, ...]] = []
     redraws = 0
@@ -43,7 +45,7 @@ def select_faults(slots, seed: int, q, k, v, dtype: int, prm: orc.Params, bit_lo
                 redraws += 1
                 continue
             _, _, dg = orc.efta_rows(Q[row:row + 1], np.array([row]), K, V, prm, [f[2:]])
-            ok = orc.fault_is_robust(dg) and len(dg["flipped"]) == 1 and not orc.fp32_is_fragile(dg["flipped"][0][1], f[2])
+            ok = orc.fault_is_robust(dg) and len(dg["flipped"]) == 1 and not orc.fp32_is_fragile(dg["flipped"][0][1], f[2], f[6])
             if ok:
                 accepted.append(f)
                 break
@@ -51,6 +53,16 @@ def select_faults(slots, seed: int, q, k, v, dtype: int, prm: orc.Params, bit_lo
         else:
             raise RuntimeError(f"no robust fault found for slot {(b, h, slot)}")
     return synth.faults_to_array(accepted), redraws
+
+
+MAX_SKIP_SHARE = 0.6
+
+
+def assert_skip_share(skipped: int, accepted: int, bound: float = MAX_SKIP_SHARE) -> None:
+    """The fault selector may pass over ill-posed candidates, but not over most of them: a filter
+    that rejects the bulk of the stream would hide a real disagreement behind "ill-posed"."""
+    share = skipped / max(1, skipped + accepted)
+    assert share <= bound, f"{skipped} of {skipped + accepted} fault candidates skipped ({share:.0%} > {bound:.0%})"
 
 
 def oracle_rows(q, k, v, dtype: int, prm: orc.Params, b: int, h: int, rows: np.ndarray, faults: np.ndarray):

@@ -197,7 +197,8 @@ def test_long_ragged_sequence_on_sampled_rows():
         ma, rf = H.tolerance_ok(out[0, h][rows], clean)
         assert ev == set() and ma <= 2e-3 and rf <= 1e-3, (h, ma, rf)
     slots = [(0, h, 0, (synth.ST_S,)) for h in range(Hh)] + [(0, h, 1, (synth.ST_OACC,)) for h in range(Hh)]
-    faults, _ = H.select_faults(slots, 0x10A7, q, k, v, dtype, prm, 24, 30)
+    faults, redraws = H.select_faults(slots, 0x10A7, q, k, v, dtype, prm, 24, 30)
+    H.assert_skip_share(redraws, len(faults))
     out2, rep2, _ = H.run_gpu(q, k, v, dtype, True, faults)
     expected = set()
     for (b, h) in sorted({(int(f[0]), int(f[1])) for f in faults}):

@@ -43,6 +43,7 @@ def test_element_wide_parity(shape, dtype, causal, scale):
     slots = [(b, h, s, (stage,)) for b in range(B) for h in range(Hh)
              for s, stage in enumerate((synth.ST_OACC, synth.ST_OACC, synth.ST_ROWSUM, synth.ST_S, synth.ST_EXP, synth.ST_S))]
     faults, redraws = H.select_faults(slots, 0xE1E1 + N, q, k, v, dtype, prm, 20, 30)
+    H.assert_skip_share(redraws, len(faults))
     out2, rep2, _ = H.run_gpu(q, k, v, dtype, causal, faults, stride=1)
     expected = set()
     got, ref = [], []

@@ -104,7 +104,7 @@ def test_injected_faults_are_detected_located_and_repaired_as_the_oracle_says(m,
     print(f"[gemm faults] m={m} n={n} k={k} bits={bits} dtype={dtype}", flush=True)
     xb, wb = synth.gen_linear(m, n, k, synth.LINEAR_SEED_BASE + 2, dtype=dtype)
     X, W = f64(xb, dtype), f64(wb, dtype)
-    prm = orc.Params(bf16=dtype == synth.BF16)
+    prm = orc.Params()
     # a value restored from bf16 checksum words carries their 16-bit precision
     tol_fix = TOL32 if dtype == synth.F16 else 4e-3
     faults = select_faults(X, W, prm, 32, synth.LINEAR_SEED_BASE + 3, *bits)
@@ -213,7 +213,7 @@ def test_token_fold_variant_matches_the_oracle(m, n, k, dtype, out_dtype):
     print(f"[gemm token fold] m={m} n={n} k={k} dtype={dtype} out={out_dtype}", flush=True)
     xb, wb = synth.gen_linear(m, n, k, synth.LINEAR_SEED_BASE + 6, dtype=dtype)
     X, W = f64(xb, dtype), f64(wb, dtype)
-    prm = orc.Params(bf16=dtype == synth.BF16, fold_tokens=True)
+    prm = orc.Params(fold_tokens=True)
     ulp = {ftgemm.F32: 0.0, ftgemm.F16: 2.0 ** -10, ftgemm.BF16: 2.0 ** -7}[out_dtype]
     tol = max(TOL32 if dtype == synth.F16 else 4e-3, ulp)
     want = orc.linear_clean(X, W)

@@ -8,6 +8,7 @@ the launch configuration the benchmark times.
 import numpy as np
 import pytest
 
+from oracle import efta_oracle as orc
 from paper_2504_02211_amd import synth
 import ft_harness as H
 
@@ -50,12 +51,21 @@ def test_workload_parity(cfg):
     ma, rf = H.tolerance_ok(np.concatenate(got), np.concatenate(ref))
     print(f"[parity] workload {cfg}: fault-free max-abs {ma:.3e} rel-Frobenius {rf:.3e}", flush=True)
     assert ma <= MAX_ABS and rf <= REL_FRO
+    if cfg >= 3:
+        # one whole head, every row and every element, against the definition
+        b, h = heads[len(heads) // 2]
+        Q, K, V = (H.head_f64(x, w.dtype, b, h) for x in (q, k, v))
+        full = orc.attention_clean(Q, K, V, prm.scale, prm.causal)
+        ma, rf = H.tolerance_ok(out[b, h], full)
+        print(f"[parity] workload {cfg}: whole head ({b},{h}), {w.seq} rows: max-abs {ma:.3e} rel-Frobenius {rf:.3e}", flush=True)
+        assert ma <= MAX_ABS and rf <= REL_FRO
 
     # ---- run B: the workload's seeded bit flips
     faults, redraws = H.select_faults(synth.workload_fault_slots(cfg), synth.FAULT_SEED_BASE + cfg, q, k, v, w.dtype,
                                       prm, w.bit_lo, w.bit_hi)
     assert len(faults) == w.batch * w.heads * w.faults_per_head
     print(f"[parity] workload {cfg}: {len(faults)} faults ({redraws} candidates skipped)", flush=True)
+    H.assert_skip_share(redraws, len(faults))
     out2, rep2, _ = H.run_gpu(q, k, v, w.dtype, w.causal, faults)
     expected = set()
     got, ref = [], []

@@ -43,6 +43,7 @@ def test_per_step_parity(shape, dtype, causal, scale, mode):
              for s, stage in enumerate((synth.ST_OACC, synth.ST_OACC, synth.ST_ROWSUM, synth.ST_S, synth.ST_EXP, synth.ST_S))]
     # (duplication compares exactly: with it every bit of an exponential or of the row-sum is in range)
     faults, redraws = H.select_faults(slots, 0x57EA + N, q, k, v, dtype, prm, 10 if mode == 1 else 0, 30 if mode == 1 else 31)
+    H.assert_skip_share(redraws, len(faults))
     out2, rep2, _ = H.run_gpu(q, k, v, dtype, causal, faults, per_step=mode)
     expected = set()
     got, ref = [], []

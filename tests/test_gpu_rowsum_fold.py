@@ -42,6 +42,7 @@ def test_rowsum_fold_parity(shape, dtype, causal, scale):
     slots = [(b, h, s, (stage,)) for b in range(B) for h in range(Hh)
              for s, stage in enumerate((synth.ST_ROWSUM, synth.ST_ROWSUM, synth.ST_OACC, synth.ST_S, synth.ST_EXP, synth.ST_ROWSUM))]
     faults, redraws = H.select_faults(slots, 0xF01E + N, q, k, v, dtype, prm, 10, 30)
+    H.assert_skip_share(redraws, len(faults))
     all_faults = faults
     for mode, correct in ((1, True), (2, False)):
         prm.correct = correct

@@ -33,43 +33,20 @@ def test_encode_w_against_loops():
             assert abs(c2[c, k] - sum((l + 1) * Wb[c + 8 * l, k] for l in range(4))) < 1e-12
 
 
-def test_two_words_hold_the_checksum():
-    rng = np.random.default_rng(3)
-    c = rng.standard_normal((8, 64)) * 37.0
-    hi, lo = orc.two_fp16_words(c)
-    assert np.array_equal(hi, hi.astype(np.float16).astype(np.float64))
-    assert np.array_equal(lo, lo.astype(np.float16).astype(np.float64))
-    assert np.max(np.abs(hi + lo - c) / np.abs(c)) < 2.0 ** -20
-    # a value fp16 holds exactly needs no low word
-    hi, lo = orc.two_fp16_words(np.array([1024.0, -0.5, 3.0]))
-    assert np.array_equal(lo, np.zeros(3))
-
-
-def test_bf16_words():
-    """bf16 keeps 8 significant bits: rounding is to nearest even, two words hold 16 bits."""
-    x = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -7, -3.1415926, 65280.0, 0.0])
-    r = orc.round_bf16(x)
-    assert r.tolist()[:4] == [1.0, 1.0, 1.0 + 2.0 ** -6, 1.0 + 2.0 ** -7] and r[5] == 65280.0 and r[6] == 0.0
-    assert abs(r[4] + 3.1415926) <= 2.0 ** -7
-    rng = np.random.default_rng(33)
-    c = rng.standard_normal((8, 64)) * 11.0
-    hi, lo = orc.two_fp16_words(c, bf16=True)
-    assert np.array_equal(hi, orc.round_bf16(hi)) and np.array_equal(lo, orc.round_bf16(lo))
-    assert np.max(np.abs(hi + lo - c) / np.abs(c)) < 2.0 ** -15
-    assert np.max(np.abs(hi - c) / np.abs(c)) <= 2.0 ** -8
-
-
-def test_bf16_inputs_stay_below_the_threshold_and_faults_are_repaired():
+def test_fault_free_residual_is_rounding_only():
+    """The oracle rounds nowhere: on real-valued operands the fault-free statistic is float64
+    rounding (orders of magnitude below the threshold), and a flipped bit is located and restored
+    to the exact product."""
     rng = np.random.default_rng(34)
-    X = orc.round_bf16(rng.standard_normal((8, 256)))
-    W = orc.round_bf16(rng.standard_normal((512, 256)) / 16)
-    prm = orc.Params(bf16=True)
+    X = rng.standard_normal((8, 256))
+    W = rng.standard_normal((512, 256)) / 16
+    prm = orc.Params()
     Yref = X @ W.T
     Y, ev, dg = orc.ftgemm(X, W, prm)
-    assert ev == [] and 0.0 < dg["res_max"] < 0.5
+    assert ev == [] and dg["res_max"] < 1e-8
     Y, ev, _ = orc.ftgemm(X, W, prm, [(5, 300, 24)])
     assert ev == [(5, 300, 1)]
-    assert np.max(np.abs(Y - Yref)) < 2e-3          # restored from bf16 checksum words: 16 bits
+    assert np.max(np.abs(Y - Yref)) < 1e-12
 
 
 def test_checksum_identity_is_exact_on_integers():

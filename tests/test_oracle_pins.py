@@ -425,6 +425,16 @@ def test_bitflip_and_fragility_helpers():
     assert orc.fp32_is_fragile(1.0, ST_EXP) and orc.fp32_is_fragile(0.0, ST_S)
     assert not orc.fp32_is_fragile(0.75, ST_EXP) and not orc.fp32_is_fragile(3.1, ST_S)
     assert orc.fp32_is_fragile(4.0001, ST_S) and orc.fp32_is_fragile(1e-40, ST_EXP)
+    # row-sum, mantissa bit 20 of a value in [4, 8) weighs 0.5: 5.25 is a quarter away from the
+    # next multiple (bit certain), 5.5 + 2^-10 is not (a sum rounded elsewhere may see the bit clear);
+    # bits below 10 never matter, exponent bits are not subject to this rule
+    assert not orc.fp32_is_fragile(5.25, ST_ROWSUM, 20)
+    assert orc.fp32_is_fragile(5.5 + 2.0 ** -10, ST_ROWSUM, 20) and orc.fp32_is_fragile(5.5 - 2.0 ** -10, ST_ROWSUM, 20)
+    assert orc.fp32_is_fragile(5.25, ST_ROWSUM, 12)           # weight 2^-9: always within the rounding distance
+    assert not orc.fp32_is_fragile(5.5 + 2.0 ** -10, ST_ROWSUM, 5) and not orc.fp32_is_fragile(5.5 + 2.0 ** -10, ST_ROWSUM, 27)
+    for b in range(10, 23):                                  # the rule is about the bit it names
+        w = 2.0 ** (b - 23) * 4.0
+        assert bitflip32(5.25, b) in (5.25 + w, 5.25 - w)
     assert orc.fault_is_robust({"lambda_ratio": 10.0, "o_ratio": 1e-9, "l_distance": 0.5})
     assert not orc.fault_is_robust({"lambda_ratio": 1.5, "o_ratio": 1e-9, "l_distance": 0.5})
     assert not orc.fault_is_robust({"lambda_ratio": 0.0, "o_ratio": 0.0, "l_distance": 1e-5})
