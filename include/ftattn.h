@@ -174,6 +174,30 @@ int ftattn_destroy(ftattn_ctx* ctx);
  * message of the last failed ftattn_create of the calling thread. */
 const char* ftattn_last_error(const ftattn_ctx* ctx);
 
+/* For callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  The same pass as ftattn_create + ftattn_forward (same
+ * kernels, default verification scheme: per_step 0, stride 8; any ft_mode, rowsum_fold, mask and
+ * type), without a context: the encoded key / value tiles, the counters and the event log live in
+ * one array of FTATTN_STATIC_SCRATCH_MIB MiB that is part of the library's device code and that
+ * every GPU the library runs on holds until the process ends.  The call allocates and frees
+ * nothing, on the host or on the device, and is two kernel launches on `hip_stream`.
+ *   cfg           host pointer, as for ftattn_create (defaults resolved the same way; max_events is
+ *                 capped at 4096).  A shape whose encoded tiles do not fit the array fails with
+ *                 FTATTN_EUNSUPPORTED and a message that names both sizes; nothing is launched.
+ *   q, k, v, o    device pointers owned by the caller, as for ftattn_forward.
+ *   n_events_dev  device pointer to one int32 owned by the caller, or NULL: when the pass has run
+ *                 it holds the number of events the checks raised (0 on a fault-free pass).
+ * No fault list: the injector needs staging buffers.  All calls on one GPU share that GPU's
+ * array, which keeps the previous call's contents; every part a pass reads is rewritten by its
+ * own encode launch first, so calls may follow each other on one stream in any order of shapes,
+ * but calls that overlap in time on one GPU (different streams, different threads) race.
+ * On failure returns a negative code; ftattn_static_last_error() then returns the calling
+ * thread's message (a fixed buffer, never allocated). */
+#define FTATTN_STATIC_SCRATCH_MIB 64
+int ftattn_forward_static(const ftattn_config* cfg, const void* q, const void* k, const void* v, void* o,
+                          int32_t* n_events_dev, void* hip_stream);
+const char* ftattn_static_last_error(void);
+
 #ifdef __cplusplus
 }
 #endif

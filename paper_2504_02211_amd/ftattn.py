@@ -22,7 +22,9 @@ FT_OFF, FT_CORRECT, FT_DETECT = 0, 1, 2
 OK, EINVAL, EUNSUPPORTED, EHIP, ENOMEM = 0, -1, -2, -3, -4
 
 EXPORTS = ("ftattn_create", "ftattn_get_config", "ftattn_forward", "ftattn_report", "ftattn_destroy",
-           "ftattn_last_error", "ftattn_set_timing", "ftattn_get_timing")
+           "ftattn_last_error", "ftattn_set_timing", "ftattn_get_timing", "ftattn_forward_static",
+           "ftattn_static_last_error")
+STATIC_SCRATCH_MIB = 64
 
 
 class Config(C.Structure):
@@ -85,8 +87,12 @@ def load_library() -> C.CDLL:
     lib.ftattn_get_timing.argtypes = [C.c_void_p, C.POINTER(C.c_float)]
     lib.ftattn_last_error.argtypes = [C.c_void_p]
     lib.ftattn_last_error.restype = C.c_char_p
+    lib.ftattn_forward_static.argtypes = [C.POINTER(Config), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_void_p]
+    lib.ftattn_static_last_error.argtypes = []
+    lib.ftattn_static_last_error.restype = C.c_char_p
     for n in ("ftattn_create", "ftattn_get_config", "ftattn_forward", "ftattn_report", "ftattn_destroy",
-              "ftattn_set_timing", "ftattn_get_timing"):
+              "ftattn_set_timing", "ftattn_get_timing", "ftattn_forward_static"):
         getattr(lib, n).restype = C.c_int
     _lib = lib
     return lib
@@ -119,6 +125,21 @@ class Report:
         e = self.events
         return set(zip(e["b"].tolist(), e["h"].tolist(), e["check"].tolist(), e["kv_tile"].tolist(),
                        e["row"].tolist(), e["col"].tolist()))
+
+
+def forward_static(q, k, v, o, batch: int, heads: int, seq: int, head_dim: int, in_dtype: int, causal: bool,
+                   out_dtype: int = F32, ft_mode: int = FT_CORRECT, softmax_scale: float = 0.0, n_events=None,
+                   stream: int = 0, device: int = 0, rowsum_fold: bool = False) -> None:
+    """ftattn_forward_static: one pass without a context and without any allocation, on the
+    library's static scratch array.  n_events: a device int32 tensor (or address) that receives the
+    number of events, or None."""
+    lib = load_library()
+    cfg = Config(C.sizeof(Config), batch, heads, seq, head_dim, in_dtype, out_dtype, int(bool(causal)), softmax_scale,
+                 ft_mode, 8, 0, 0, 0.0, 0.0, 0.0, int(bool(rowsum_fold)), 0, 0, device)
+    ptr = lambda t: C.c_void_p(None if t is None else t if isinstance(t, int) else t.data_ptr())
+    rc = lib.ftattn_forward_static(C.byref(cfg), ptr(q), ptr(k), ptr(v), ptr(o), ptr(n_events), C.c_void_p(stream))
+    if rc != OK:
+        raise FtAttnError(rc, lib.ftattn_static_last_error().decode())
 
 
 class FtAttn:
