@@ -28,48 +28,134 @@ def useful_flops(w) -> float:
     return 4.0 * w.head_dim * n * w.batch * w.heads
 
 
-def measured_traffic(cfg: int):
-    """HBM bytes per launch of the FT kernel from the committed rocprofv3 counter summary (None if absent)."""
-    path = os.path.join(ROOT, "profiles", "ftattn_main_cfg5_long_sequence_hbm_traffic.txt")
-    if cfg != 5 or not os.path.exists(path):
-        return None
+def kernel_sources_sha() -> str:
+    """Hash of the HIP sources; a committed counter summary names the hash it was measured on."""
+    import hashlib
+    h = hashlib.sha1()
+    d = os.path.join(ROOT, "paper_2504_02211_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        h.update(name.encode())
+        h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()[:12]
+
+
+def profile_traffic(name: str):
+    """(HBM bytes per launch of the protected kernel, note) from the committed rocprofv3 counter summary
+    profiles/<name>.  The figure is NOT measured by this run (a counter run needs rocprofv3 around the
+    process): it is reported only when the summary was taken on the kernel sources of this tree."""
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return None, "no committed counter summary"
+    val, sha = None, None
     for line in open(path):
         if line.startswith("traffic_bytes_per_launch_ft"):
-            return float(line.split("=")[1])
-    return None
+            val = float(line.split("=")[1])
+        if line.startswith("kernel_sources_sha"):
+            sha = line.split("=")[1].strip()
+    if val is None:
+        return None, "summary holds no traffic figure"
+    if sha != kernel_sources_sha():
+        return None, f"profiles/{name} was measured on other kernel sources ({sha}); not reported"
+    return val, f"from profiles/{name} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this command on these kernel sources), not measured in this run"
 
 
-def time_variant(torch, ftattn, w, tq, tk, tv, ft_mode, steps, warmup, block_m, rowsum_fold=False, per_step=0, stride=8):
-    o = torch.empty((w.batch, w.heads, w.seq, w.head_dim), dtype=torch.float32, device="cuda")
-    ctx = ftattn.FtAttn(w.batch, w.heads, w.seq, w.head_dim, w.dtype, w.causal, ft_mode=ft_mode, block_m=block_m,
-                        rowsum_fold=rowsum_fold, per_step=per_step, stride=stride)
+class ClockSampler:
+    """Samples the shader clock from sysfs while kernels run (outside the timed K steps)."""
+
+    def __init__(self):
+        import glob
+        self.paths = [p for p in glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk") if os.access(p, os.R_OK)]
+        self.samples = []
+        self._stop = False
+        self._thread = None
+
+    def _read(self):
+        for p in self.paths:
+            try:
+                for line in open(p):
+                    if "*" in line:
+                        return float(line.split(":")[1].replace("Mhz", "").replace("MHz", "").replace("*", "").strip())
+            except Exception:
+                pass
+        return None
+
+    def __enter__(self):
+        import threading
+        if self.paths:
+            def loop():
+                while not self._stop:
+                    v = self._read()
+                    if v:
+                        self.samples.append(v)
+                    time.sleep(0.01)
+            self._thread = threading.Thread(target=loop, daemon=True)
+            self._thread.start()
+        return self
+
+    def __exit__(self, *a):
+        self._stop = True
+        if self._thread:
+            self._thread.join()
+
+    def summary(self):
+        if not self.samples:
+            return None
+        x = sorted(self.samples)
+        return {"median_mhz": x[len(x) // 2], "min_mhz": x[0], "max_mhz": x[-1], "samples": len(x),
+                "source": "pp_dpm_sclk sampled every 10 ms during the interleaved launches"}
+
+
+def stats(xs):
+    x = sorted(xs)
+    return {"median": round(x[len(x) // 2], 4), "min": round(x[0], 4), "mean": round(sum(x) / len(x), 4), "n": len(x)}
+
+
+def time_pair(torch, ftattn, w, tq, tk, tv, steps, warmup, block_m, rowsum_fold=False, per_step=0, stride=8):
+    """Times the protected pass and its twin with every check compiled out.
+
+    (1) `steps` protected steps back to back between two synchronisations: the step time the metric
+        is quoted on.
+    (2) max(50, steps) launches of each variant, interleaved (protected, unprotected, protected, ...),
+        each bracketed by HIP events the library records on the launch stream: median, minimum and
+        mean of the encode kernel, the fused kernel and their sum; the overhead is taken from these
+        interleaved medians, so that clock and thermal drift hit both variants alike."""
+    shape = (w.batch, w.heads, w.seq, w.head_dim)
+    o = torch.empty(shape, dtype=torch.float32, device="cuda")
+    mk = lambda mode, **kw: ftattn.FtAttn(w.batch, w.heads, w.seq, w.head_dim, w.dtype, w.causal, ft_mode=mode, block_m=block_m, **kw)
+    ft = mk(ftattn.FT_CORRECT, rowsum_fold=rowsum_fold, per_step=per_step, stride=stride)
+    un = mk(ftattn.FT_OFF)
     stream = torch.cuda.Stream()
     sp = stream.cuda_stream
-    for _ in range(warmup):
-        ctx.forward(tq, tk, tv, o, None, sp)
+    for _ in range(max(10, warmup)):
+        ft.forward(tq, tk, tv, o, None, sp)
+        un.forward(tq, tk, tv, o, None, sp)
     torch.cuda.synchronize()
-    e0 = torch.cuda.Event(enable_timing=True)
-    e1 = torch.cuda.Event(enable_timing=True)
-    with torch.cuda.stream(stream):
-        e0.record(stream)
-        for _ in range(steps):
-            ctx.forward(tq, tk, tv, o, None, sp)
-        e1.record(stream)
-    torch.cuda.synchronize()
-    ms_step = e0.elapsed_time(e1) / steps
-    # per-kernel durations from HIP events the library records on the same stream
-    ctx.set_timing(True)
-    enc, main = [], []
-    for _ in range(min(steps, 10)):
-        ctx.forward(tq, tk, tv, o, None, sp)
-        a, b = ctx.get_timing()
-        enc.append(a); main.append(b)
-    ctx.set_timing(False)
-    rep = ctx.report()
-    info = dict(ms_step=ms_step, ms_encode=sum(enc) / len(enc), ms_main=sum(main) / len(main), events=rep.n_events,
-                rechecks=rep.recheck_entries, block_m=ctx.config.block_m, block_n=ctx.config.block_n)
-    ctx.close()
-    return info
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    res = {}
+    for name, ctx in (("ft", ft), ("un", un)):
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            e0.record(stream)
+            for _ in range(steps):
+                ctx.forward(tq, tk, tv, o, None, sp)
+            e1.record(stream)
+        torch.cuda.synchronize()
+        res[name] = {"ms_step": e0.elapsed_time(e1) / steps}
+    ft.set_timing(True); un.set_timing(True)
+    t = {"ft": ([], []), "un": ([], [])}
+    with ClockSampler() as clk:
+        for _ in range(max(50, steps)):
+            for name, ctx in (("ft", ft), ("un", un)):
+                ctx.forward(tq, tk, tv, o, None, sp)
+                a, b = ctx.get_timing()
+                t[name][0].append(a); t[name][1].append(b)
+    for name in ("ft", "un"):
+        enc, main = t[name]
+        res[name].update(encode=stats(enc), main=stats(main), both=stats([a + b for a, b in zip(enc, main)]))
+    rep = ft.report()
+    res["ft"].update(events=rep.n_events, rechecks=rep.recheck_entries, block_m=ft.config.block_m, block_n=ft.config.block_n)
+    ft.close(); un.close()
+    return res["ft"], res["un"], clk.summary()
 
 
 def cpu_baseline(w, q, k, v, n_heads=4):
@@ -100,14 +186,7 @@ def cpu_baseline(w, q, k, v, n_heads=4):
 
 
 def linear_traffic():
-    """HBM bytes per launch of the FT linear kernel from the committed rocprofv3 counter summary (None if absent)."""
-    path = os.path.join(ROOT, "profiles", "ftgemm_main_ffn_16k_16k_4k_counters.txt")
-    if not os.path.exists(path):
-        return None
-    for line in open(path):
-        if line.startswith("traffic_bytes_per_launch_ft"):
-            return float(line.split("=")[1])
-    return None
+    return profile_traffic("ftgemm_main_ffn_16k_16k_4k_counters.txt")
 
 
 def bench_linear(args):
@@ -167,7 +246,7 @@ def bench_linear(args):
            "ms_kernel": round(ft["ms_kernel"], 4), "ms_kernel_unprotected": round(un["ms_kernel"], 4),
            "events": ft["events"], "residual_max": round(ft["resmax"], 5),
            "roofline": {"bound": "mfma", "achieved": round(tfk, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                        "frac": round(tfk / MFMA_PEAK_TFLOPS, 4), "traffic": linear_traffic(),
+                        "frac": round(tfk / MFMA_PEAK_TFLOPS, 4), "traffic": linear_traffic()[0], "traffic_source": linear_traffic()[1],
                         "kernel": "ftgemm_main (FT linear layer)", "algorithmic_flops_per_launch": flops}}
     if args.pmc_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -198,7 +277,7 @@ def bench_linear(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", type=int, default=5)
     ap.add_argument("--block-m", type=int, default=0)
@@ -230,7 +309,6 @@ def main():
 
     import torch
     from paper_2504_02211_amd import ftattn, synth
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
 
     def to_dev(bits, dtype):
         import numpy as np
@@ -243,19 +321,19 @@ def main():
         w = synth.WORKLOADS[cfg]
         q, k, v = synth.gen_workload(cfg)
         tq, tk, tv = (to_dev(x, w.dtype) for x in (q, k, v))
-        ft = time_variant(torch, ftattn, w, tq, tk, tv, ftattn.FT_CORRECT, args.steps, args.warmup, args.block_m, args.rowsum_fold, args.per_step, args.stride)
-        un = time_variant(torch, ftattn, w, tq, tk, tv, ftattn.FT_OFF, args.steps, args.warmup, args.block_m)
-        results[cfg] = (w, ft, un)
+        results[cfg] = (w,) + time_pair(torch, ftattn, w, tq, tk, tv, args.steps, args.warmup, args.block_m, args.rowsum_fold, args.per_step, args.stride)
         if cfg == args.workload:
             keep = (q, k, v)
         del tq, tk, tv
         torch.cuda.empty_cache()
 
-    w, ft, un = results[args.workload]
+    w, ft, un, clocks = results[args.workload]
     fl = useful_flops(w)
     tf = fl / (ft["ms_step"] * 1e-3) / 1e12
     tf_un = fl / (un["ms_step"] * 1e-3) / 1e12
-    tf_kernel = fl / (ft["ms_main"] * 1e-3) / 1e12
+    tf_kernel = fl / (ft["main"]["mean"] * 1e-3) / 1e12
+    default_mode = not (args.rowsum_fold or args.per_step or args.stride != 8 or args.block_m)
+    traffic, traffic_note = profile_traffic(f"ftattn_main_cfg{w.cfg}_{w.name.replace(' ', '_').replace('-', '_')}_hbm_traffic.txt") if default_mode else (None, "non-default mode")
     out = {
         "metric": "FT-attention TFLOP/s at 1 GPU, % overhead vs unprotected, % MFMA peak",
         "value": round(tf, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -267,21 +345,29 @@ def main():
                    "rowsum_protection": "extra checksum fold" if args.rowsum_fold else "range restriction",
                    "verification": ("unified", "after every step", "after every step, duplicated softmax")[args.per_step]},
         "unprotected_tflops": round(tf_un, 2), "unprotected_ms_per_step": round(un["ms_step"], 4),
-        "ft_overhead_pct": round((ft["ms_step"] / un["ms_step"] - 1) * 100, 2),
+        # overhead of the whole step (encode + fused kernel) from the interleaved per-launch medians;
+        # the back-to-back figure next to it is the ratio of the two K-step means
+        "ft_overhead_pct": round((ft["both"]["median"] / un["both"]["median"] - 1) * 100, 2),
+        "ft_overhead_pct_back_to_back": round((ft["ms_step"] / un["ms_step"] - 1) * 100, 2),
         "mfma_peak_pct": round(tf / MFMA_PEAK_TFLOPS * 100, 2),
-        "ms_encode": round(ft["ms_encode"], 4), "ms_fused_kernel": round(ft["ms_main"], 4),
-        "ms_fused_kernel_unprotected": round(un["ms_main"], 4),
+        "per_launch_ms": {"protocol": f"{ft['main']['n']} launches per variant, protected / unprotected interleaved, HIP events on the launch stream",
+                          "encode": ft["encode"], "fused_kernel": ft["main"], "step": ft["both"],
+                          "encode_unprotected": un["encode"], "fused_kernel_unprotected": un["main"], "step_unprotected": un["both"]},
+        "shader_clock": clocks,
+        "ms_encode": ft["encode"]["mean"], "ms_fused_kernel": ft["main"]["mean"],
+        "ms_fused_kernel_unprotected": un["main"]["mean"],
         "fast_path_rechecks": ft["rechecks"], "events": ft["events"],
         "roofline": {"bound": "mfma", "achieved": round(tf_kernel, 2), "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(tf_kernel / MFMA_PEAK_TFLOPS, 4), "traffic": measured_traffic(w.cfg) if not (args.rowsum_fold or args.per_step or args.stride != 8) else None,
+                     "frac": round(tf_kernel / MFMA_PEAK_TFLOPS, 4), "traffic": traffic, "traffic_source": traffic_note,
+                     "frac_at_median": round(fl / (ft["main"]["median"] * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, 4),
                      "kernel": "ftattn_main (fused FT attention)", "algorithmic_flops_per_launch": fl},
     }
     if args.all_workloads:
         out["other_workloads"] = {
             f"cfg{c}": {"ft_tflops": round(useful_flops(ww) / f_["ms_step"] / 1e9, 2),
                         "unprotected_tflops": round(useful_flops(ww) / u_["ms_step"] / 1e9, 2),
-                        "ft_overhead_pct": round((f_["ms_step"] / u_["ms_step"] - 1) * 100, 2)}
-            for c, (ww, f_, u_) in results.items() if c != args.workload}
+                        "ft_overhead_pct": round((f_["both"]["median"] / u_["both"]["median"] - 1) * 100, 2)}
+            for c, (ww, f_, u_, _) in results.items() if c != args.workload}
     if args.pmc_copy:
         src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
         dst = torch.empty_like(src)

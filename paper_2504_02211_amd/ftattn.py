@@ -127,6 +127,32 @@ class Report:
                        e["row"].tolist(), e["col"].tolist()))
 
 
+_ITEMSIZE = {F16: 2, BF16: 2, F32: 4}
+_TORCH_NAME = {F16: "torch.float16", BF16: "torch.bfloat16", F32: "torch.float32"}
+
+
+def device_pointer(t, name: str, n_elems: int, dtype: int, device: int) -> C.c_void_p:
+    """Address of a caller's tensor for the C ABI.  An integer is taken as a device address as it
+    is; an object with the tensor protocol (torch) is checked first -- element type, element count,
+    contiguity, device -- because the library can only see a raw pointer, and a tensor of the
+    wrong size or type would turn into an out-of-bounds access on the GPU instead of an error."""
+    if isinstance(t, int):
+        return C.c_void_p(t)
+    if not hasattr(t, "data_ptr"):
+        raise TypeError(f"{name}: expected a device tensor or an integer address, got {type(t).__name__}")
+    if hasattr(t, "is_cuda") and not t.is_cuda:
+        raise ValueError(f"{name}: tensor is not on a GPU")
+    if hasattr(t, "device") and getattr(t.device, "index", None) not in (None, device):
+        raise ValueError(f"{name}: tensor is on device {t.device.index}, the context on device {device}")
+    if hasattr(t, "is_contiguous") and not t.is_contiguous():
+        raise ValueError(f"{name}: tensor is not contiguous")
+    if hasattr(t, "dtype") and str(t.dtype) != _TORCH_NAME[dtype]:
+        raise ValueError(f"{name}: tensor is {t.dtype}, expected {_TORCH_NAME[dtype]}")
+    if hasattr(t, "numel") and t.numel() != n_elems:
+        raise ValueError(f"{name}: tensor has {t.numel()} elements, the configured shape has {n_elems}")
+    return C.c_void_p(t.data_ptr())
+
+
 def forward_static(q, k, v, o, batch: int, heads: int, seq: int, head_dim: int, in_dtype: int, causal: bool,
                    out_dtype: int = F32, ft_mode: int = FT_CORRECT, softmax_scale: float = 0.0, n_events=None,
                    stream: int = 0, device: int = 0, rowsum_fold: bool = False) -> None:
@@ -136,8 +162,11 @@ def forward_static(q, k, v, o, batch: int, heads: int, seq: int, head_dim: int, 
     lib = load_library()
     cfg = Config(C.sizeof(Config), batch, heads, seq, head_dim, in_dtype, out_dtype, int(bool(causal)), softmax_scale,
                  ft_mode, 8, 0, 0, 0.0, 0.0, 0.0, int(bool(rowsum_fold)), 0, 0, device)
-    ptr = lambda t: C.c_void_p(None if t is None else t if isinstance(t, int) else t.data_ptr())
-    rc = lib.ftattn_forward_static(C.byref(cfg), ptr(q), ptr(k), ptr(v), ptr(o), ptr(n_events), C.c_void_p(stream))
+    n = batch * heads * seq * head_dim
+    ptr = lambda t, name, dt: C.c_void_p(None) if t is None else device_pointer(t, name, n, dt, device)
+    nev = C.c_void_p(None) if n_events is None else C.c_void_p(n_events if isinstance(n_events, int) else n_events.data_ptr())
+    rc = lib.ftattn_forward_static(C.byref(cfg), ptr(q, "q", in_dtype), ptr(k, "k", in_dtype), ptr(v, "v", in_dtype),
+                                   ptr(o, "o", out_dtype), nev, C.c_void_p(stream))
     if rc != OK:
         raise FtAttnError(rc, lib.ftattn_static_last_error().decode())
 
@@ -164,14 +193,17 @@ class FtAttn:
     def forward(self, q, k, v, o, faults: Optional[np.ndarray] = None, stream: int = 0) -> None:
         """q, k, v, o: objects with data_ptr() (torch device tensors) or integer device addresses.
         faults: int32 array [n, 7] of (b, h, stage, kv_tile, row, col, bit)."""
-        ptr = lambda t: C.c_void_p(t if isinstance(t, int) else t.data_ptr())
+        c = self.config
+        ne = c.batch * c.heads * c.seq * c.head_dim
+        ptr = lambda t, name, dt: device_pointer(t, name, ne, dt, c.device)
         n = 0
         fp = None
         if faults is not None and len(faults):
             fa = np.ascontiguousarray(faults, dtype=np.int32).reshape(-1, 7)
             n = fa.shape[0]
             fp = fa.ctypes.data_as(C.POINTER(Fault))
-        rc = self.lib.ftattn_forward(self.handle, ptr(q), ptr(k), ptr(v), ptr(o), fp, n, C.c_void_p(stream))
+        rc = self.lib.ftattn_forward(self.handle, ptr(q, "q", c.in_dtype), ptr(k, "k", c.in_dtype), ptr(v, "v", c.in_dtype),
+                                     ptr(o, "o", c.out_dtype), fp, n, C.c_void_p(stream))
         if rc != OK:
             raise FtAttnError(rc, self.lib.ftattn_last_error(self.handle).decode())
 

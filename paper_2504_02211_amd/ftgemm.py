@@ -116,12 +116,15 @@ class FtGemm:
         if rc != OK:
             raise FtGemmError(rc, self.lib.ftgemm_last_error(self.handle).decode())
 
-    @staticmethod
-    def _ptr(t) -> C.c_void_p:
-        return C.c_void_p(t if isinstance(t, int) else t.data_ptr())
+    def _ptr(self, t, name: str) -> C.c_void_p:
+        """Device address of x / w / y, checked against the context's shape (see ftattn.device_pointer)."""
+        from .ftattn import device_pointer
+        c = self.config
+        n_elems, dt = {"x": (c.m * c.k, c.in_dtype), "w": (c.n * c.k, c.in_dtype), "y": (c.m * c.n, c.out_dtype)}[name]
+        return device_pointer(t, name, n_elems, dt, c.device)
 
     def encode_weights(self, w, stream: int = 0) -> None:
-        self._check(self.lib.ftgemm_encode_weights(self.handle, self._ptr(w), C.c_void_p(stream)))
+        self._check(self.lib.ftgemm_encode_weights(self.handle, self._ptr(w, "w"), C.c_void_p(stream)))
 
     def forward(self, x, w, y, faults: Optional[np.ndarray] = None, stream: int = 0) -> None:
         """x, w, y: objects with data_ptr() (torch device tensors) or integer device addresses.
@@ -132,7 +135,7 @@ class FtGemm:
             fa = np.ascontiguousarray(faults, dtype=np.int32).reshape(-1, 3)
             n = fa.shape[0]
             fp = fa.ctypes.data_as(C.POINTER(Fault))
-        self._check(self.lib.ftgemm_forward(self.handle, self._ptr(x), self._ptr(w), self._ptr(y), fp, n,
+        self._check(self.lib.ftgemm_forward(self.handle, self._ptr(x, "x"), self._ptr(w, "w"), self._ptr(y, "y"), fp, n,
                                             C.c_void_p(stream)))
 
     def report(self) -> Report:

@@ -149,3 +149,25 @@ def test_candidate_streams_respect_the_mask_and_the_seu_rule():
     assert not synth.conflicts((0, 0, synth.ST_EXP, 2, 5, 130, 3), [(0, 0, synth.ST_S, 1, 5, 90, 4)])
     assert synth.conflicts((0, 0, synth.ST_OACC, 2, 5, 11, 3), [(0, 0, synth.ST_OACC, 0, 5, 3, 4)])
     assert len(list(synth.workload_fault_slots(4))) == 4 * 32 * 4
+
+
+def test_binding_checks_tensors_before_passing_raw_pointers():
+    """The C ABI sees addresses only; the binding refuses a tensor whose type, size, layout or
+    device does not fit the configured shape (it would be an out-of-bounds access on the GPU)."""
+    class FakeDevice:
+        index = 0
+    class FakeTensor:
+        def __init__(self, n, dtype="torch.float16", contiguous=True, cuda=True):
+            self._n, self.dtype, self._c, self.is_cuda, self.device = n, dtype, contiguous, cuda, FakeDevice()
+        def data_ptr(self): return 4096
+        def numel(self): return self._n
+        def is_contiguous(self): return self._c
+    ok = ftattn.device_pointer(FakeTensor(64), "q", 64, ftattn.F16, 0)
+    assert ok.value == 4096 and ftattn.device_pointer(12345, "q", 64, ftattn.F16, 0).value == 12345
+    for bad in (FakeTensor(63), FakeTensor(64, "torch.bfloat16"), FakeTensor(64, contiguous=False), FakeTensor(64, cuda=False)):
+        with pytest.raises(ValueError):
+            ftattn.device_pointer(bad, "q", 64, ftattn.F16, 0)
+    with pytest.raises(ValueError):
+        ftattn.device_pointer(FakeTensor(64), "q", 64, ftattn.F16, 1)
+    with pytest.raises(TypeError):
+        ftattn.device_pointer(object(), "q", 64, ftattn.F16, 0)

@@ -44,9 +44,12 @@ def test_static_entry_point_matches_the_context_path_on_two_calls_in_a_row():
 
 def test_static_entry_point_rejects_what_does_not_fit():
     x = torch.zeros(16, dtype=torch.float16, device="cuda")
+    a = x.data_ptr()                                     # raw addresses: the C entry point must refuse before any launch
     with pytest.raises(ftattn.FtAttnError) as ei:        # 8 x 16 x 2048 x 64: 100 MB of encoded tiles
-        ftattn.forward_static(x, x, x, x, 8, 16, 2048, 64, synth.BF16, True)
+        ftattn.forward_static(a, a, a, a, 8, 16, 2048, 64, synth.BF16, True)
     assert ei.value.code == ftattn.EUNSUPPORTED and "scratch" in str(ei.value)
     with pytest.raises(ftattn.FtAttnError) as ei:
-        ftattn.forward_static(x, x, x, None, 1, 1, 64, 64, synth.F16, False)
+        ftattn.forward_static(a, a, a, None, 1, 1, 64, 64, synth.F16, False)
     assert ei.value.code == ftattn.EINVAL
+    with pytest.raises(ValueError):                      # the binding refuses a tensor of the wrong size
+        ftattn.forward_static(x, x, x, x, 1, 1, 64, 64, synth.F16, False)
