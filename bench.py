@@ -274,6 +274,59 @@ def bench_linear(args):
     return 0
 
 
+def bench_decoupled(args):
+    """The comparison of Section 4.1 on this library: the decoupled three-kernel scheme (ABFT-GEMM I,
+    DMR row-softmax, ABFT-GEMM II with S and P in device memory) against the fused kernel, both
+    protected, on one workload; a JSON line of its own."""
+    import numpy as np
+    import torch
+    from paper_2504_02211_amd import ftattn, ftdecoupled, synth
+    w = synth.WORKLOADS[args.workload]
+    q, k, v = synth.gen_workload(args.workload)
+    tdt = torch.float16 if w.dtype == synth.F16 else torch.bfloat16
+    tq, tk, tv = (torch.from_numpy(x.view(np.int16)).cuda().view(tdt) for x in (q, k, v))
+    shape = (w.batch, w.heads, w.seq, w.head_dim)
+    o = torch.empty(shape, dtype=torch.float32, device="cuda")
+    o2 = torch.empty(shape, dtype=torch.float32, device="cuda")
+    dec = ftdecoupled.FtDecoupled(*shape, w.dtype, w.causal)
+    fus = ftattn.FtAttn(*shape, w.dtype, w.causal)
+    stream = torch.cuda.Stream()
+    sp = stream.cuda_stream
+    n = max(3, min(args.steps, 10))
+    for _ in range(3):
+        dec.forward(tq, tk, tv, o, None, sp)
+        fus.forward(tq, tk, tv, o2, None, sp)
+    torch.cuda.synchronize()
+    dec.set_timing(True); fus.set_timing(True)
+    td, tf_ = [], []
+    for _ in range(n):
+        dec.forward(tq, tk, tv, o, None, sp)
+        td.append(dec.get_timing())
+        fus.forward(tq, tk, tv, o2, None, sp)
+        tf_.append(sum(fus.get_timing()))
+    rep = dec.report()
+    total, s_and_p = dec.footprint()
+    diff = float((o - o2).abs().max())
+    med = lambda xs: sorted(xs)[len(xs) // 2]
+    g1, sm, g2 = (med([t[i] for t in td]) for i in range(3))
+    ms_dec, ms_fus = med([sum(t) for t in td]), med(tf_)
+    fl = useful_flops(w)
+    out = {"metric": "decoupled (three-kernel) FT attention vs the fused kernel, both protected, 1 GPU",
+           "value": round(fl / ms_dec / 1e9, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": n, "warmup": 3,
+           "ms_per_step": round(ms_dec, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "f16", "data": "synthetic",
+           "config": {"workload": f"cfg{w.cfg} {w.name}: batch {w.batch}, heads {w.heads}, seq {w.seq}, head_dim {w.head_dim}, "
+                                  f"{'bf16' if w.dtype else 'fp16'} in, fp32 out, {'causal' if w.causal else 'non-causal'}, fault-free"},
+           "ms_abft_gemm1": round(g1, 4), "ms_dmr_softmax": round(sm, 4), "ms_abft_gemm2": round(g2, 4),
+           "fused_ms_per_step": round(ms_fus, 4), "fused_speedup_over_decoupled": round(ms_dec / ms_fus, 2),
+           "decoupled_device_bytes": total, "decoupled_s_and_p_bytes": s_and_p,
+           "fused_scratch_bytes": int(w.batch * w.heads * ((w.seq + 63) // 64) * ((64 + 32) * w.head_dim + (w.head_dim + 32) * 64) * 2),
+           "events": rep.n_events, "max_abs_difference_of_the_two_outputs": diff}
+    dec.close(); fus.close()
+    print(json.dumps(out))
+    return 0
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -291,6 +344,8 @@ def main():
     ap.add_argument("--stride", type=int, choices=(8, 1), default=8,
                     help="attention: checksum stride; 1 = the traditional checksum (one class per tile row) the paper "
                          "compares its stride-8 tensor checksum with")
+    ap.add_argument("--decoupled", action="store_true",
+                    help="time the decoupled three-kernel scheme of the paper's Section 3.1 against the fused kernel (its own JSON line)")
     ap.add_argument("--linear", action="store_true",
                     help="time the protected feed-forward GEMM instead of attention (its own JSON line)")
     ap.add_argument("--linear-dtype", choices=("fp16", "bf16"), default="fp16")
@@ -306,6 +361,8 @@ def main():
 
     if args.linear:
         return bench_linear(args)
+    if args.decoupled:
+        return bench_decoupled(args)
 
     import torch
     from paper_2504_02211_amd import ftattn, synth

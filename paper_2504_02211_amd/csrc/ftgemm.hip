@@ -67,6 +67,29 @@ static gemm_fn select_gemm(bool ft, bool inject, bool bf, bool ragged) {
 }
 static size_t gemm_lds(bool ft) { return ft ? GStage<true>::LDS_TOTAL : GStage<false>::LDS_TOTAL; }
 
+namespace ftgemm {
+hipError_t gemm_allow_lds(int k) {
+  for (int v = 0; v < 8; ++v) {
+    hipError_t he = hipFuncSetAttribute((const void*)select_gemm((v & 1) != 0, (v & 2) != 0, (v & 4) != 0, k % GBK != 0),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds((v & 1) != 0));
+    if (he != hipSuccess) return he;
+  }
+  return hipSuccess;
+}
+hipError_t gemm_launch_encode_w(const uint16_t* w, uint16_t* wc, int n, int k, bool bf16, hipStream_t st, int batch,
+                                long long bs_w, long long bs_wc) {
+  dim3 grid((n + GBN - 1) / GBN, (k / 8 + 31) / 32, batch);
+  if (bf16) ftgemm_encode_w<true><<<grid, 256, 0, st>>>(w, wc, n, k, bs_w, bs_wc);
+  else ftgemm_encode_w<false><<<grid, 256, 0, st>>>(w, wc, n, k, bs_w, bs_wc);
+  return hipGetLastError();
+}
+hipError_t gemm_launch(const GArgs& a, bool ft, bool inject, bool bf16, hipStream_t st, int batch) {
+  gemm_fn f = select_gemm(ft, inject, bf16, a.K % GBK != 0);
+  hipLaunchKernelGGL(f, dim3(a.Tm * a.Tn, batch), dim3(GWAVES * 64), gemm_lds(ft), st, a);
+  return hipGetLastError();
+}
+}  // namespace ftgemm
+
 extern "C" int ftgemm_create(const ftgemm_config* cfg, ftgemm_ctx** out) {
   if (!cfg || !out) return gfail(nullptr, FTGEMM_EINVAL, "null argument");
   *out = nullptr;
@@ -121,9 +144,7 @@ extern "C" int ftgemm_create(const ftgemm_config* cfg, ftgemm_ctx** out) {
   GCREATE_TRY(hipMemset(c->wc, 0, n_wc * 2));
   GCREATE_TRY(hipMemset(c->d_ev_count, 0, sizeof(int32_t)));
   GCREATE_TRY(hipMemset(c->d_resmax, 0, sizeof(uint32_t)));
-  for (int v = 0; v < 8; ++v)
-    GCREATE_TRY(hipFuncSetAttribute((const void*)select_gemm((v & 1) != 0, (v & 2) != 0, (v & 4) != 0, e.k % GBK != 0),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds((v & 1) != 0)));
+  GCREATE_TRY(gemm_allow_lds(e.k));
   GCREATE_TRY(hipDeviceSynchronize());
 #undef GCREATE_TRY
   *out = c;
@@ -193,6 +214,7 @@ extern "C" int ftgemm_forward(ftgemm_ctx* c, const void* x, const void* w, void*
   a.y = y; a.out_dtype = e.out_dtype;
   a.M = tr ? e.n : e.m; a.N = tr ? e.m : e.n; a.K = e.k; a.Tm = c->Tm; a.Tn = c->Tn;
   a.transposed = tr ? 1 : 0;
+  a.bs_x = a.bs_w = a.bs_wc = a.bs_y_bytes = a.bs_events = 0;
   a.tau_rel = e.tau_rel; a.tau_abs = e.tau_abs;
   a.correct = e.ft_mode == FTGEMM_FT_CORRECT ? 1 : 0;
   a.faults = c->d_faults; a.n_faults = n_faults;

@@ -72,6 +72,10 @@ struct GArgs {
   int32_t* ev_count;
   int32_t max_events;
   uint32_t* resmax;        // float bits of a non-negative value
+  // batch of independent products (blockIdx.y): element strides between consecutive problems of x, w,
+  // wc and the event log, byte stride of y; counters and residual maxima are one per problem.  All
+  // zero for a single product.
+  long long bs_x, bs_w, bs_wc, bs_y_bytes, bs_events;
   int32_t transposed;      // 1: the kernel's (token, feature) is the caller's (column, row) of Y: checksums over the
                            // caller's token rows; results are stored, and events named, with the two exchanged
 };
@@ -94,8 +98,10 @@ template <bool FT> struct GStage {
 // rounded, low = the remainder rounded).  Rows beyond N count as zero.
 template <bool BF>
 __global__ __launch_bounds__(256) void ftgemm_encode_w(const uint16_t* __restrict__ w, uint16_t* __restrict__ wc,
-                                                       int N, int K) {
+                                                       int N, int K, long long bs_w = 0, long long bs_wc = 0) {
   typedef uint16_t u16x8 __attribute__((ext_vector_type(8)));
+  w += (size_t)blockIdx.z * bs_w;        // batch of weight matrices
+  wc += (size_t)blockIdx.z * bs_wc;
   const int tn = blockIdx.x, tid = threadIdx.x;
   const int cls = tid >> 5, ch = blockIdx.y * 32 + (tid & 31);
   if (ch * 8 >= K) return;
@@ -142,7 +148,14 @@ __device__ __forceinline__ void log_gemm_event(const GArgs& a, int row, int col,
 // RAG: K is not a multiple of the K step (the last step is partly empty); a separate instantiation so that the
 // regular case carries none of its selects
 template <bool FT, bool INJ, bool BF, bool RAG = false>
-__global__ __launch_bounds__(GWAVES * 64) void ftgemm_main(const GArgs a) {
+__global__ __launch_bounds__(GWAVES * 64) void ftgemm_main(const GArgs a0) {
+  GArgs a = a0;
+  {
+    const size_t by = blockIdx.y;          // problem of the batch
+    a.x += by * a0.bs_x; a.w += by * a0.bs_w; a.wc += by * a0.bs_wc;
+    a.y = reinterpret_cast<char*>(a0.y) + by * a0.bs_y_bytes;
+    a.events += by * a0.bs_events; a.ev_count += by; a.resmax += by;
+  }
   using S = GStage<FT>;
   constexpr int NA = FT ? 9 : 8;          // A operands (32-row blocks of W, + the checksum block) per k-step
   constexpr int NKS = GBK / 16;           // k-steps of 16 per stage
@@ -400,5 +413,13 @@ __global__ __launch_bounds__(GWAVES * 64) void ftgemm_main(const GArgs a) {
       }
   }
 }
+
+// Launch helpers defined next to the kernels' instantiations (ftgemm.hip), for other host code of
+// the library that runs the same protected product on buffers of its own (the decoupled attention
+// baseline).  None of them allocates or synchronises.
+hipError_t gemm_allow_lds(int k);
+hipError_t gemm_launch_encode_w(const uint16_t* w, uint16_t* wc, int n, int k, bool bf16, hipStream_t st,
+                                int batch = 1, long long bs_w = 0, long long bs_wc = 0);
+hipError_t gemm_launch(const GArgs& a, bool ft, bool inject, bool bf16, hipStream_t st, int batch = 1);
 
 }  // namespace ftgemm

@@ -1,0 +1,130 @@
+"""GPU parity of the decoupled, operation-level fault-tolerant attention (Section 3.1: ABFT-GEMM I,
+DMR row-softmax, ABFT-GEMM II; include/ftdecoupled.h) against its oracle, through the C ABI.
+Bars as for the fused path: fault-free O within max-abs 2e-3 / relative Frobenius 1e-3 of the
+definition and no event; with seeded faults of all four stages the event sets (stage, row, column)
+are identical to the oracle's and the output stays within the same tolerance of the oracle's."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import decoupled_oracle as dorc
+from oracle import efta_oracle as eorc
+from oracle import ftgemm_oracle as gorc
+from paper_2504_02211_amd import ftattn, ftdecoupled, synth
+import ft_harness as H
+
+pytestmark = pytest.mark.gpu
+
+MAX_ABS, REL_FRO = 2e-3, 1e-3
+
+
+def _run(q, k, v, dtype, causal, faults=None, ft_mode=ftdecoupled.FT_CORRECT):
+    B, Hh, N, d = q.shape
+    ctx = ftdecoupled.FtDecoupled(B, Hh, N, d, dtype, causal, ft_mode=ft_mode)
+    tq, tk, tv = (H.to_torch(x, dtype) for x in (q, k, v))
+    o = torch.full((B, Hh, N, d), float("nan"), dtype=torch.float32, device="cuda")
+    ctx.forward(tq, tk, tv, o, faults, torch.cuda.current_stream().cuda_stream)
+    rep = ctx.report()
+    cfg, fp = ctx.config, ctx.footprint()
+    ctx.close()
+    return o.double().cpu().numpy(), rep, cfg, fp
+
+
+def _select_faults(Q, K, V, prm, rng, n, stages=(0, 1, 2, 3)):
+    """n seeded faults on distinct rows of one head, each clear of every threshold by a factor 4."""
+    N, d = Q.shape
+    out, rows, tried = [], set(), 0
+    while len(out) < n and tried < 40 * n:
+        tried += 1
+        st = int(rng.choice(stages))
+        row = int(rng.integers(0, N))
+        if row in rows:
+            continue
+        if st == dorc.ST_GEMM2:
+            col = int(rng.integers(0, d))
+        elif st == dorc.ST_GEMM1:
+            col = int(rng.integers(0, N))
+        else:
+            col = int(rng.integers(0, row + 1 if prm.causal else N))
+        f = (st, row, col, int(rng.integers(12, 31)))
+        # a single row of the head decides: the checks of the three steps are row-local
+        _, _, dg = dorc.decoupled_attention(Q[row:row + 1], K, V, prm, [f], row_idx=[row])
+        flipped = dg["gemm1"]["flipped"] + dg["gemm2"]["flipped"]
+        if not dorc.fault_is_robust(dg, prm) or any(gorc.fp32_is_fragile(x) for x in flipped):
+            continue
+        out.append(f); rows.add(row)
+    return out, tried
+
+
+@pytest.mark.parametrize("shape,dtype,causal", [((1, 2, 300, 64), synth.F16, True), ((2, 2, 520, 128), synth.BF16, False),
+                                                ((1, 1, 77, 64), synth.BF16, True), ((1, 3, 641, 128), synth.F16, True)])
+def test_decoupled_parity(shape, dtype, causal):
+    B, Hh, N, d = shape
+    print(f"[decoupled] shape {shape} dtype {dtype} causal {causal}", flush=True)
+    q, k, v = synth.gen_qkv(shape, dtype, 0xDEC0 + N)
+    out, rep, cfg, (total, sp) = _run(q, k, v, dtype, causal)
+    assert rep.n_events == 0 and rep.retried_rows == 0
+    assert sp == B * Hh * N * N * 4 + B * Hh * N * ((N + 7) // 8 * 8) * 2 and total > sp
+    prm = dorc.Params(scale=float(cfg.softmax_scale), causal=causal, tau_rel=float(cfg.tau_rel), eps_dmr=float(cfg.eps_dmr))
+    got, ref = [], []
+    heads = [(b, h) for b in range(B) for h in range(Hh)]
+    for (b, h) in heads:
+        Q, K, V = (H.head_f64(x, dtype, b, h) for x in (q, k, v))
+        got.append(out[b, h]); ref.append(eorc.attention_clean(Q, K, V, prm.scale, causal))
+    ma, rf = H.tolerance_ok(np.concatenate(got), np.concatenate(ref))
+    print(f"[decoupled] fault-free max-abs {ma:.3e} rel-Frobenius {rf:.3e}", flush=True)
+    assert ma <= MAX_ABS and rf <= REL_FRO
+    # the same kernels with the checks off give the same output
+    out0, rep0, _, _ = _run(q, k, v, dtype, causal, ft_mode=ftdecoupled.FT_OFF)
+    assert rep0.n_events == 0 and np.abs(out0 - out).max() <= 1e-5
+
+    # ---- seeded flips of all four stages, five per head
+    rng = np.random.default_rng(0xDEC1 + N)
+    faults, per_head, tried = [], {}, 0
+    for (b, h) in heads:
+        Q, K, V = (H.head_f64(x, dtype, b, h) for x in (q, k, v))
+        fl, t = _select_faults(Q, K, V, prm, rng, 5)
+        tried += t
+        assert len(fl) == 5
+        per_head[(b, h)] = fl
+        faults += [(b, h) + f for f in fl]
+    H.assert_skip_share(tried - len(faults), len(faults))
+    fa = np.array(faults, np.int32)
+    out2, rep2, _, _ = _run(q, k, v, dtype, causal, fa)
+    expected, got, ref = set(), [], []
+    for (b, h) in heads:
+        Q, K, V = (H.head_f64(x, dtype, b, h) for x in (q, k, v))
+        O, ev, _ = dorc.decoupled_attention(Q, K, V, prm, per_head[(b, h)])
+        expected |= {(b, h) + e for e in ev}
+        got.append(out2[b, h]); ref.append(O)
+    assert rep2.n_events_dropped == 0
+    assert rep2.event_set() == expected, (sorted(rep2.event_set() - expected)[:5], sorted(expected - rep2.event_set())[:5])
+    assert len(expected) >= len(faults) // 2
+    assert rep2.retried_rows == len({e for e in expected if e[2] in (dorc.ST_EXP, dorc.ST_PNORM)})
+    ma, rf = H.tolerance_ok(np.concatenate(got), np.concatenate(ref))
+    print(f"[decoupled] {len(faults)} faults, {len(expected)} events identical; max-abs {ma:.3e} rel-Frobenius {rf:.3e}", flush=True)
+    assert ma <= MAX_ABS and rf <= REL_FRO
+
+
+def test_decoupled_rejects_bad_faults_and_long_rows_run_from_memory():
+    shape = (1, 1, 64, 64)
+    q, k, v = synth.gen_qkv(shape, synth.F16, 0xDEC7)
+    ctx = ftdecoupled.FtDecoupled(1, 1, 64, 64, synth.F16, True)
+    tq, tk, tv = (H.to_torch(x, synth.F16) for x in (q, k, v))
+    o = torch.empty(shape, dtype=torch.float32, device="cuda")
+    for bad in ([0, 0, 1, 3, 9, 20], [0, 0, 3, 3, 64, 20], [0, 0, 0, 64, 0, 20], [0, 1, 0, 0, 0, 20], [0, 0, 0, 0, 0, 32]):
+        with pytest.raises(ftdecoupled.FtDecError) as ei:
+            ctx.forward(tq, tk, tv, o, np.array([bad], np.int32))
+        assert ei.value.code == ftdecoupled.EINVAL
+    ctx.close()
+    # a row longer than the LDS staging area (32 KB of fp32 scores) is read from memory instead
+    shape = (1, 1, 33000, 64)
+    q, k, v = synth.gen_qkv(shape, synth.F16, 0xDEC8)
+    out, rep, cfg, _ = _run(q, k, v, synth.F16, True)
+    assert rep.n_events == 0
+    rows = np.array([0, 1, 255, 256, 20000, 32999])
+    Q, K, V = (H.head_f64(x, synth.F16, 0, 0) for x in (q, k, v))
+    ref = eorc.attention_clean(Q[rows], K, V, float(cfg.softmax_scale), True, rows)
+    ma, rf = H.tolerance_ok(out[0, 0][rows], ref)
+    assert ma <= MAX_ABS and rf <= REL_FRO

@@ -7,7 +7,7 @@ import re
 import numpy as np
 import pytest
 
-from paper_2504_02211_amd import ftattn, ftgemm, synth
+from paper_2504_02211_amd import ftattn, ftdecoupled, ftgemm, synth
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -20,12 +20,13 @@ def _declared_functions(header, prefix):
 
 def test_library_exports_every_declared_symbol():
     lib = ftattn.load_library()
-    for header, prefix, exports in (("ftattn.h", "ftattn", ftattn.EXPORTS), ("ftgemm.h", "ftgemm", ftgemm.EXPORTS)):
+    for header, prefix, exports in (("ftattn.h", "ftattn", ftattn.EXPORTS), ("ftgemm.h", "ftgemm", ftgemm.EXPORTS),
+                                    ("ftdecoupled.h", "ftdec", ftdecoupled.EXPORTS)):
         names = _declared_functions(header, prefix)
         assert set(names) == set(exports)
         for n in names:
             assert hasattr(lib, n), n
-    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["ftattn.h", "ftgemm.h"]
+    assert sorted(os.listdir(os.path.join(ROOT, "include"))) == ["ftattn.h", "ftdecoupled.h", "ftgemm.h"]
 
 
 def test_struct_layouts_match_header():
@@ -171,3 +172,22 @@ def test_binding_checks_tensors_before_passing_raw_pointers():
         ftattn.device_pointer(FakeTensor(64), "q", 64, ftattn.F16, 1)
     with pytest.raises(TypeError):
         ftattn.device_pointer(object(), "q", 64, ftattn.F16, 0)
+
+
+def test_decoupled_create_rejects_bad_configs_without_a_device():
+    lib = ftdecoupled.load_library()
+    assert C.sizeof(ftdecoupled.Config) == 13 * 4 and C.sizeof(ftdecoupled.Fault) == 24 == C.sizeof(ftdecoupled.Event)
+    def create(**kw):
+        base = dict(struct_size=C.sizeof(ftdecoupled.Config), batch=1, heads=1, seq=64, head_dim=64, in_dtype=0, causal=0,
+                    softmax_scale=0.0, ft_mode=1, tau_rel=0.0, eps_dmr=0.0, max_events=0, device=0)
+        base.update(kw)
+        h = C.c_void_p()
+        return lib.ftdec_create(C.byref(ftdecoupled.Config(**base)), C.byref(h))
+    assert create(struct_size=8) == ftdecoupled.EINVAL
+    assert create(seq=0) == ftdecoupled.EINVAL
+    assert create(head_dim=60) == ftdecoupled.EUNSUPPORTED and create(head_dim=512) == ftdecoupled.EUNSUPPORTED
+    assert create(in_dtype=2) == ftdecoupled.EINVAL and create(causal=2) == ftdecoupled.EINVAL
+    assert create(ft_mode=2) == ftdecoupled.EINVAL
+    assert b"ft_mode" in lib.ftdec_last_error(None)
+    assert lib.ftdec_forward(None, None, None, None, None, None, 0, None) == ftdecoupled.EINVAL
+    assert lib.ftdec_report(None, None) == ftdecoupled.EINVAL and lib.ftdec_destroy(None) == ftdecoupled.EINVAL
