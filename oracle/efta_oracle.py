@@ -12,7 +12,7 @@ Two results are defined here.
     maximum).  The tiled method reaches exactly this when no fault occurs
     (Section 2.1, eq. (2)-(8)), so this is the reference for fault-free output.
 
-``efta_rows``
+``efta_rows`` (= ``efta_rows_unified`` unless a verification variant is asked for)
     Algorithm 1 ("EFTA with unified verification", Section 3.4) taken step by
     step in float64 for a set of query rows of one (batch, head): tensor-checksum
     encoding (eq. (13), (14)), GEMM I with its two checksum products (eq. (15),
@@ -228,11 +228,207 @@ Fault = Tuple[int, int, int, int, int]     # (stage, kv_tile, row, col, bit)
 Event = Tuple[int, int, int, int]          # (check, kv_tile, row, col)
 
 
+def _softmax_part(Srows, vrows, m_old, sc):
+    """Reduce max and element-wise exp of one key tile (Algorithm 1: m_ij, P_ij) over the unmasked entries."""
+    with np.errstate(all="ignore"):
+        mh = np.where(vrows, sc * Srows, -np.inf).max(axis=1)
+        mn = np.maximum(m_old, mh)
+        x = sc * Srows - mn[:, None]
+        P = np.where(vrows, np.exp(x), 0.0)
+    return mh, mn, x, P
+
+
+def efta_rows_unified(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
+                      prm: Params, faults: Sequence[Fault] = (),
+                      max_shift: Optional[Dict[Tuple[int, int], float]] = None
+                      ) -> Tuple[np.ndarray, List[Event], Dict[str, float]]:
+    """Algorithm 1 ("EFTA with unified verification") for query rows ``row_idx`` of one head, top to
+    bottom in the paper's order, with none of the verification variants.
+
+    Q: [n, d] float64 (rows row_idx of the head's query matrix), K, V: [N, d].
+    Returns (O [n, d], sorted events, diagnostics).  Diagnostics hold the largest check statistic
+    over all evaluated checks relative to its threshold (``lambda_ratio``, ``o_ratio``) and the
+    smallest relative distance of a final row-sum to its range boundaries (``l_distance``); the fault
+    generator uses them to keep clear of decisions that hinge on rounding.  ``flipped`` lists
+    (stage, value before the flip) for every fault that was applied.
+
+    ``max_shift`` maps (kv_tile, row) to an error added to the running maximum the moment it is
+    formed (Section 3.4, case 1: such an error needs no protection because it cancels between
+    numerator and denominator); tests use it to show exactly that.
+    """
+    s, Bc, sc = prm.stride, prm.block_n, prm.scale
+    n, d = Q.shape
+    N = K.shape[0]
+    assert Bc % s == 0 and d % s == 0
+    assert not (prm.rowsum_fold or prm.per_step or prm.softmax_dmr)
+    nK, nV = Bc // s, d // s
+    row_idx = np.asarray(row_idx, dtype=np.int64)
+    pos = {int(r): i for i, r in enumerate(row_idx)}
+    by_tile: Dict[Tuple[int, int], List[Tuple[int, int, int]]] = {}
+    for (st, kt, row, col, bit) in faults:
+        if int(row) in pos:
+            by_tile.setdefault((int(st), int(kt)), []).append((pos[int(row)], int(col), int(bit)))
+
+    m = np.full(n, -np.inf)          # running row maximum
+    ell = np.zeros(n)                # running row-sum
+    lower = np.zeros(n)              # its lower bound: sum over key tiles of exp(tile maximum - m)
+    Ot = np.zeros((n, d))            # un-normalised output and its two checksums
+    Oc1 = np.zeros((n, s))
+    Oc2 = np.zeros((n, s))
+    events: List[Event] = []
+    flipped: List[Tuple[int, float]] = []
+    lam_ratio = 0.0
+
+    for j in range((N + Bc - 1) // Bc):
+        k0 = j * Bc
+        act = np.flatnonzero(row_idx >= k0) if prm.causal else np.arange(n)      # rows that see this key tile
+        if act.size == 0:
+            break
+        keys = k0 + np.arange(Bc)
+        Kj = np.zeros((Bc, d)); Vj = np.zeros((Bc, d))
+        kv = min(N, k0 + Bc) - k0
+        Kj[:kv] = K[k0:k0 + kv]; Vj[:kv] = V[k0:k0 + kv]
+        valid = np.broadcast_to(keys[None, :] < N, (act.size, Bc)).copy()
+        if prm.causal:
+            valid &= keys[None, :] <= row_idx[act, None]
+        loc = {int(a): i for i, a in enumerate(act)}
+
+        # ---- encode tensor checksums (eq. (13), (14))
+        Kc1, Kc2 = encode_k(Kj, s)
+        Vc1, Vc2 = encode_v(Vj, s)
+        # ---- GEMM I with its checksum products (eq. (15), (16)); injection point S
+        Qa = Q[act]
+        S = Qa @ Kj.T
+        Sc1 = Qa @ Kc1.T
+        Sc2 = Qa @ Kc2.T
+        for (ri, col, bit) in by_tile.get((ST_S, j), []):
+            if ri in loc:
+                flipped.append((ST_S, float(S[loc[ri], col - k0])))
+                S[loc[ri], col - k0] = bitflip32(S[loc[ri], col - k0], bit)
+        # ---- reduce max, element-wise exp; injection point exp
+        m_hat, m_new, x, P = _softmax_part(S, valid, m[act], sc)
+        for (jt, row), dm in (max_shift or {}).items():
+            if jt == j and int(row) in pos and pos[int(row)] in loc:
+                i = loc[pos[int(row)]]
+                m_new[i] += dm
+                x[i] = sc * S[i] - m_new[i]
+                P[i] = np.where(valid[i], np.exp(x[i]), 0.0)
+        touched = np.zeros_like(valid)
+        for (ri, col, bit) in by_tile.get((ST_EXP, j), []):
+            if ri in loc and valid[loc[ri], col - k0]:
+                flipped.append((ST_EXP, float(P[loc[ri], col - k0])))
+                P[loc[ri], col - k0] = bitflip32(P[loc[ri], col - k0], bit)
+                touched[loc[ri], col - k0] = True
+        # ---- unified verification of GEMM I, subtraction and exp (Section 3.4, case 2):
+        # lambda = ln prod P - (scale * check1_eff - n_valid * m) per (row, class)
+        with np.errstate(all="ignore"):
+            sum1, _ = fold(S, s)
+            R1 = Sc1 - sum1
+            e = np.where(touched & valid, np.log(P) - x, 0.0)
+            E, _ = fold(e, s)
+            lam = E - sc * R1
+        has_valid = valid.reshape(act.size, nK, s).any(axis=1)
+        with np.errstate(invalid="ignore"):
+            ok = np.abs(lam) <= prm.eps1
+        det = has_valid & ~ok
+        fin = has_valid & np.isfinite(lam)
+        if fin.any():
+            lam_ratio = max(lam_ratio, float(np.abs(lam[fin]).max()) / prm.eps1)
+        if (has_valid & ~np.isfinite(lam)).any():
+            lam_ratio = np.inf
+        redo = []
+        for (i, c) in zip(*np.nonzero(det)):
+            cols = c + s * np.arange(nK)
+            with np.errstate(invalid="ignore"):
+                linear = not (sc * abs(R1[i, c]) <= prm.eps1 / 2)
+            if linear:
+                # a fault of GEMM I: located with the second checksum, restored from the first (text after eq. (16))
+                lstar, val = locate_and_restore(S[i, cols], Sc1[i, c], Sc2[i, c])
+                col = k0 + int(cols[lstar]) if lstar >= 0 else -1
+                events.append((CHECK_S, j, int(row_idx[act[i]]), col))
+                if prm.correct and lstar >= 0:
+                    S[i, cols[lstar]] = val
+                    redo.append(i)
+            else:
+                # a fault of the exponentiation: recomputed
+                with np.errstate(all="ignore"):
+                    good = np.exp(x[i, cols])
+                for l in range(nK):
+                    if valid[i, cols[l]] and touched[i, cols[l]] and P[i, cols[l]] != good[l]:
+                        events.append((CHECK_EXP, j, int(row_idx[act[i]]), k0 + int(cols[l])))
+                        if prm.correct:
+                            P[i, cols[l]] = good[l]
+        for i in sorted(set(redo)):      # a repaired score: the row's maximum and exponentials for this tile again
+            mh, mn, xx, PP = _softmax_part(S[i:i + 1], valid[i:i + 1], m[act[i]:act[i] + 1], sc)
+            m_hat[i], m_new[i], x[i], P[i] = mh[0], mn[0], xx[0], PP[0]
+        # ---- reduce sum, GEMM II with rescale and its checksum products; injection points row-sum, output accumulator
+        with np.errstate(all="ignore"):
+            alpha = np.exp(m[act] - m_new)
+            ell[act] = alpha * ell[act] + P.sum(axis=1)
+            lower[act] = alpha * lower[act] + np.where(np.isfinite(m_hat), np.exp(m_hat - m_new), 0.0)
+            for (ri, col, bit) in by_tile.get((ST_ROWSUM, j), []):
+                flipped.append((ST_ROWSUM, float(ell[ri])))
+                ell[ri] = bitflip32(ell[ri], bit)
+            Ot[act] = alpha[:, None] * Ot[act] + P @ Vj
+            Oc1[act] = alpha[:, None] * Oc1[act] + P @ Vc1
+            Oc2[act] = alpha[:, None] * Oc2[act] + P @ Vc2
+            for (ri, col, bit) in by_tile.get((ST_OACC, j), []):
+                flipped.append((ST_OACC, float(Ot[ri, col])))
+                Ot[ri, col] = bitflip32(Ot[ri, col], bit)
+        m[act] = m_new
+
+    # ---- range restriction of the row-sum with substitution of the lower bound (Section 3.4, case 3; "optimized EFTA")
+    U = np.minimum(row_idx + 1, N).astype(np.float64) if prm.causal else np.full(n, float(N))
+    with np.errstate(all="ignore"):
+        in_range = (lower * (1 - prm.delta_l) <= ell) & (ell <= U * (1 + prm.delta_l))
+        dist = np.minimum(np.abs(ell / (lower * (1 - prm.delta_l)) - 1), np.abs(ell / (U * (1 + prm.delta_l)) - 1))
+    dist = np.where(np.isfinite(dist), dist, np.inf)
+    for i in np.flatnonzero(~in_range):
+        events.append((CHECK_L, -1, int(row_idx[i]), 0))
+        if prm.correct:
+            ell[i] = lower[i]
+    # ---- normalisation, then unified verification of GEMM II, rescale and normalisation
+    with np.errstate(all="ignore"):
+        O = Ot / ell[:, None]
+        C1 = Oc1 / ell[:, None]
+        C2 = Oc2 / ell[:, None]
+        sum1, _ = fold(O, s)
+        R = C1 - sum1
+        okO = np.abs(R) <= prm.tau_o
+    finR = np.isfinite(R)
+    o_ratio = float(np.abs(R[finR]).max()) / prm.tau_o if finR.any() else 0.0
+    if (~finR).any():
+        o_ratio = np.inf
+    for (i, c) in zip(*np.nonzero(~okO)):
+        cols = c + s * np.arange(nV)
+        lstar, val = locate_and_restore(O[i, cols], C1[i, c], C2[i, c])
+        events.append((CHECK_O, -1, int(row_idx[i]), int(cols[lstar]) if lstar >= 0 else -1))
+        if prm.correct and lstar >= 0:
+            O[i, cols[lstar]] = val
+    diag = {"lambda_ratio": float(lam_ratio), "o_ratio": float(o_ratio),
+            "l_distance": float(dist.min()) if n else np.inf, "l_ratio": 0.0, "flipped": flipped,
+            "lin_ratio": 0.0, "o_step_ratio": 0.0, "l_step_distance": np.inf}
+    return O, sorted(events), diag
+
+
 def efta_rows(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
               prm: Params, faults: Sequence[Fault] = (),
               max_shift: Optional[Dict[Tuple[int, int], float]] = None
               ) -> Tuple[np.ndarray, List[Event], Dict[str, float]]:
-    """Algorithm 1 for query rows ``row_idx`` of one head.
+    """Algorithm 1 for query rows ``row_idx`` of one head: ``efta_rows_unified`` (the paper's method),
+    or, when ``prm`` asks for one of the verification variants, ``efta_rows_with_modes``."""
+    if prm.rowsum_fold or prm.per_step or prm.softmax_dmr:
+        return efta_rows_with_modes(Q, row_idx, K, V, prm, faults, max_shift)
+    return efta_rows_unified(Q, row_idx, K, V, prm, faults, max_shift)
+
+
+def efta_rows_with_modes(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
+              prm: Params, faults: Sequence[Fault] = (),
+              max_shift: Optional[Dict[Tuple[int, int], float]] = None
+              ) -> Tuple[np.ndarray, List[Event], Dict[str, float]]:
+    """Algorithm 1 with the verification variants of ``Params`` (``rowsum_fold``, ``per_step``,
+    ``softmax_dmr``) for query rows ``row_idx`` of one head.  With every variant off it takes
+    exactly the steps of ``efta_rows_unified`` (a test holds the two against each other).
 
     Q: [n, d] float64 (rows row_idx of the head's query matrix), K, V: [N, d].
     Returns (O [n, d], sorted events, diagnostics).  Diagnostics hold the largest

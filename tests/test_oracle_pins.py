@@ -649,3 +649,31 @@ def test_dmr_leaves_the_matrix_products_to_their_checksums():
     assert np.abs(O - clean).max() < 1e-9
     with pytest.raises(AssertionError):
         efta_rows(Q, np.arange(N), K, V, Params(scale=0.3, causal=True, block_n=Bc, softmax_dmr=True))
+
+
+def test_unified_path_and_the_variant_function_take_the_same_steps():
+    """``efta_rows_unified`` is Algorithm 1 written out without any variant; ``efta_rows_with_modes``
+    with every variant off must agree with it bit for bit (outputs, events, diagnostics), with and
+    without faults, for both strides, masks and ragged lengths."""
+    rng = np.random.default_rng(77)
+    for (N, d, Bc, causal, stride) in ((96, 16, 32, True, 8), (70, 16, 16, False, 8), (64, 8, 64, True, 1), (50, 24, 16, True, 8)):
+        Q, K, V = (rng.standard_normal((N, d)) for _ in range(3))
+        prm = orc.Params(scale=0.4, causal=causal, block_n=Bc, stride=stride)
+        rows = np.arange(N)
+        fl = []
+        for st in (ST_S, ST_EXP, ST_ROWSUM, ST_OACC):
+            for _ in range(6):
+                row = int(rng.integers(0, N))
+                kt = int(rng.integers(0, (row if causal else N - 1) // Bc + 1))
+                hi = min(N - 1, kt * Bc + Bc - 1, row if causal else N - 1)
+                col = int(rng.integers(kt * Bc, hi + 1)) if st in (ST_S, ST_EXP) else int(rng.integers(0, d))
+                fl.append((st, kt, row, col, int(rng.integers(0, 32))))
+        for faults in ([], fl):
+            for correct in (True, False):
+                prm.correct = correct
+                a = orc.efta_rows_unified(Q, rows, K, V, prm, faults)
+                b = orc.efta_rows_with_modes(Q, rows, K, V, prm, faults)
+                assert a[1] == b[1]
+                assert np.array_equal(a[0], b[0], equal_nan=True)
+                for key in ("lambda_ratio", "o_ratio", "l_distance", "flipped"):
+                    assert a[2][key] == b[2][key] or (a[2][key] != a[2][key] and b[2][key] != b[2][key]), key
