@@ -52,6 +52,11 @@ enum { FTATTN_ST_S = 0, FTATTN_ST_EXP = 1, FTATTN_ST_ROWSUM = 2, FTATTN_ST_OACC 
 /* checks that can raise an event */
 enum { FTATTN_CHECK_S = 0, FTATTN_CHECK_EXP = 1, FTATTN_CHECK_L = 2, FTATTN_CHECK_O = 3 };
 enum { FTATTN_OK = 0, FTATTN_EINVAL = -1, FTATTN_EUNSUPPORTED = -2, FTATTN_EHIP = -3, FTATTN_ENOMEM = -4 };
+/* range_flags of the report: operands that do not survive the conversion of bf16 inputs to fp16 */
+enum { FTATTN_RANGE_OPERAND_OVERFLOW = 1,   /* a finite bf16 value of Q, K or V of magnitude >= 65536: Inf in fp16 */
+       FTATTN_RANGE_OPERAND_UNDERFLOW = 2,  /* a non-zero bf16 value below 2^-24: no significant bit left in fp16 (values
+                                               between 2^-24 and 2^-14 become subnormals, error < 2^-25, not flagged) */
+       FTATTN_RANGE_CHECKSUM_OVERFLOW = 4 };/* a tensor checksum of K or V beyond the fp16 range (either input type) */
 /* ft_mode */
 enum { FTATTN_FT_OFF = 0, FTATTN_FT_CORRECT = 1, FTATTN_FT_DETECT = 2 };
 
@@ -66,7 +71,8 @@ typedef struct {
   int32_t batch, heads, seq, head_dim; /* head_dim 64 or 128; seq >= 1 (any length) */
   int32_t in_dtype;       /* FTATTN_F16 | FTATTN_BF16.  bf16 operands are converted to fp16 on
                              entry (exact for 2^-14 <= |x| <= 65504): the contractions run on
-                             fp16 MFMA with fp32 accumulation for either input type. */
+                             fp16 MFMA with fp32 accumulation for either input type.  Values outside
+                             that range are reported in range_flags of the report. */
   int32_t out_dtype;      /* FTATTN_F32, or the input type */
   int32_t causal;         /* 0 | 1: lower-triangular mask including the diagonal */
   float softmax_scale;    /* <= 0 selects 1/sqrt(head_dim) */
@@ -148,6 +154,11 @@ typedef struct {
                                     O check, 2: row-sum / upper bound (rowsum_fold: relative row-sum
                                     residual), 3: lower bound / row-sum */
   int64_t recheck_entries;    /* how often a wave left the fast path to re-evaluate a check exactly */
+  int32_t range_flags;        /* FTATTN_RANGE_* bits, 0 when every operand and checksum kept its value: the
+                                 contractions run on fp16 MFMA for either input type, and a bf16 operand
+                                 of magnitude >= 65536 or < 2^-24, or a checksum beyond 65504, does not survive the conversion.
+                                 The pass still runs (results follow IEEE arithmetic on the converted values);
+                                 the caller decides whether to rescale its inputs. */
 } ftattn_report_view;
 
 /* Validates cfg, allocates all device scratch for this shape on cfg->device. */

@@ -28,6 +28,8 @@ struct Buffers {
   int32_t* ev_count = nullptr;
   unsigned long long* recheck = nullptr;
   uint32_t* resmax = nullptr;
+  uint32_t* range = nullptr;          // the word this call sets
+  uint32_t* range_next = nullptr;     // the word the next call sets: cleared by this call
 };
 
 struct ftattn_ctx {
@@ -42,6 +44,8 @@ struct ftattn_ctx {
   int32_t* d_ev_count = nullptr;
   unsigned long long* d_recheck = nullptr;
   uint32_t* d_resmax = nullptr;
+  uint32_t* d_range = nullptr;        // two words, used in turn by consecutive calls
+  unsigned calls = 0;
   int fault_cap = 0;
   // pinned host staging
   DevFault* h_faults = nullptr;
@@ -76,7 +80,7 @@ static void release(ftattn_ctx* c) {
   if (!c) return;
   (void)hipFree(c->kc); (void)hipFree(c->vt); (void)hipFree(c->d_faults);
   (void)hipFree(c->d_fault_off); (void)hipFree(c->d_events); (void)hipFree(c->d_ev_count);
-  (void)hipFree(c->d_recheck); (void)hipFree(c->d_resmax);
+  (void)hipFree(c->d_recheck); (void)hipFree(c->d_resmax); (void)hipFree(c->d_range);
   if (c->h_faults) (void)hipHostFree(c->h_faults);
   if (c->h_fault_off) (void)hipHostFree(c->h_fault_off);
   for (hipEvent_t e : c->ev) if (e) (void)hipEventDestroy(e);
@@ -212,6 +216,8 @@ extern "C" int ftattn_create(const ftattn_config* cfg, ftattn_ctx** out) {
   CREATE_TRY(hipMalloc((void**)&c->d_ev_count, sizeof(int32_t)));
   CREATE_TRY(hipMalloc((void**)&c->d_recheck, sizeof(unsigned long long)));
   CREATE_TRY(hipMalloc((void**)&c->d_resmax, sizeof(uint32_t) * n_rt * 4));
+  CREATE_TRY(hipMalloc((void**)&c->d_range, sizeof(uint32_t) * 2));
+  CREATE_TRY(hipMemset(c->d_range, 0, sizeof(uint32_t) * 2));
   CREATE_TRY(hipHostMalloc((void**)&c->h_faults, sizeof(DevFault) * c->fault_cap, hipHostMallocDefault));
   CREATE_TRY(hipHostMalloc((void**)&c->h_fault_off, sizeof(int32_t) * (n_rt + 1), hipHostMallocDefault));
   // the checksum rows of the encoded tiles are never written when ft_mode is OFF; keep them defined
@@ -254,9 +260,9 @@ static hipError_t launch_pass(const ftattn_config& e, const Geometry& g, const B
   const int bf = e.in_dtype == FTATTN_BF16 ? 1 : 0;
   const int kchk = ft ? 1 : 0, vchk = ft ? 1 + e.rowsum_fold : 0;
   if (D == 128)
-    ftattn_prepare<128><<<eg, 256, 0, st>>>(k, v, bf, b.kc, b.vt, N, g.Tj, kchk, vchk, b.ev_count, b.recheck, b.resmax, n_resmax);
+    ftattn_prepare<128><<<eg, 256, 0, st>>>(k, v, bf, b.kc, b.vt, N, g.Tj, kchk, vchk, b.ev_count, b.recheck, b.resmax, n_resmax, b.range, b.range_next);
   else
-    ftattn_prepare<64><<<eg, 256, 0, st>>>(k, v, bf, b.kc, b.vt, N, g.Tj, kchk, vchk, b.ev_count, b.recheck, b.resmax, n_resmax);
+    ftattn_prepare<64><<<eg, 256, 0, st>>>(k, v, bf, b.kc, b.vt, N, g.Tj, kchk, vchk, b.ev_count, b.recheck, b.resmax, n_resmax, b.range, b.range_next);
 
   KArgs a;
   a.q = q; a.q_bf16 = bf; a.kc = b.kc; a.vt = b.vt; a.o = o; a.out_dtype = e.out_dtype;
@@ -271,7 +277,7 @@ static hipError_t launch_pass(const ftattn_config& e, const Geometry& g, const B
   a.faults = b.faults;
   a.fault_off = inject ? b.fault_off : nullptr;
   a.events = b.events; a.ev_count = b.ev_count; a.max_events = e.max_events;
-  a.resmax = b.resmax; a.recheck = b.recheck;
+  a.resmax = b.resmax; a.recheck = b.recheck; a.range = b.range;
   main_fn f = e.per_step ? select_perstep(D, e.causal != 0, inject, e.per_step)
               : e.stride == 1 ? select_elementwide(D, e.causal != 0, inject)
                               : select_kernel(D, ft, e.causal != 0, inject);
@@ -333,10 +339,12 @@ extern "C" int ftattn_forward(ftattn_ctx* c, const void* q, const void* k, const
   Buffers bufs;
   bufs.kc = c->kc; bufs.vt = c->vt; bufs.faults = c->d_faults; bufs.fault_off = n_faults > 0 ? c->d_fault_off : nullptr;
   bufs.events = c->d_events; bufs.ev_count = c->d_ev_count; bufs.recheck = c->d_recheck; bufs.resmax = c->d_resmax;
+  bufs.range = c->d_range + (c->calls & 1u); bufs.range_next = c->d_range + ((c->calls + 1u) & 1u);
   hipError_t le = launch_pass(e, c->geo, bufs, q, k, v, o, n_faults > 0, st, c->timing ? c->ev : nullptr);
   if (le != hipSuccess) return fail(c, FTATTN_EHIP, std::string("launch: ") + hipGetErrorString(le));
   c->last_stream = st;
   c->ran = true;
+  ++c->calls;
   return FTATTN_OK;
 }
 
@@ -384,6 +392,9 @@ extern "C" int ftattn_report(ftattn_ctx* c, ftattn_report_view* out) {
   out->rowtile_flags = c->rowtile_flags.data();
   out->residual_max = c->resmax.data();
   out->recheck_entries = (int64_t)recheck;
+  uint32_t range = 0;
+  HIP_TRY(c, hipMemcpy(&range, c->d_range + ((c->calls - 1u) & 1u), sizeof range, hipMemcpyDeviceToHost));
+  out->range_flags = (int32_t)range;
   return FTATTN_OK;
 }
 
@@ -434,6 +445,7 @@ static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
 static std::mutex g_static_mu;
 static unsigned char* g_static_ptr[STATIC_MAX_DEVICES];      // per device, null until set up
 static bool g_static_lds[STATIC_MAX_DEVICES][2];             // kernels of head_dim 64 / 128 prepared
+static unsigned g_static_calls[STATIC_MAX_DEVICES];          // parity picks the range word of a call
 static thread_local char g_static_err[256];
 
 static int static_fail(int code, const char* what, hipError_t he = hipSuccess) {
@@ -474,6 +486,7 @@ extern "C" int ftattn_forward_static(const ftattn_config* cfg, const void* q, co
   hipError_t he = hipSetDevice(e.device);
   if (he != hipSuccess) return static_fail(FTATTN_EHIP, "hipSetDevice", he);
   unsigned char* base;
+  unsigned calls;
   {
     std::lock_guard<std::mutex> lock(g_static_mu);
     if (!g_static_ptr[e.device]) {
@@ -489,11 +502,14 @@ extern "C" int ftattn_forward_static(const ftattn_config* cfg, const void* q, co
       g_static_lds[e.device][di] = true;
     }
     base = g_static_ptr[e.device];
+    calls = g_static_calls[e.device]++;
   }
 
   Buffers bufs;
   bufs.ev_count = n_events_dev ? n_events_dev : (int32_t*)base;
   bufs.recheck = (unsigned long long*)(base + 8);
+  bufs.range = (uint32_t*)(base + 16) + (calls & 1u);
+  bufs.range_next = (uint32_t*)(base + 16) + ((calls + 1u) & 1u);
   bufs.resmax = (uint32_t*)(base + off_resmax);
   bufs.events = (ftattn_event*)(base + off_events);
   bufs.kc = (_Float16*)(base + off_kc);

@@ -61,6 +61,7 @@ struct KArgs {
   int32_t max_events;
   uint32_t* resmax;        // [BH][Ti][4], float bits of non-negative values
   unsigned long long* recheck;
+  uint32_t* range;         // FTATTN_RANGE_* bits of this call (operands that do not survive the conversion to fp16)
 };
 
 // ------------------------------------------------------------------ small helpers
@@ -135,6 +136,24 @@ __device__ __forceinline__ int key_of(int kb, int v, int hi) { return 32 * kb + 
 
 // ------------------------------------------------------------------ encode kernels
 
+// FTATTN_RANGE_* bits of 8 consecutive bf16 patterns: a finite value of magnitude 65536 or more
+// becomes Inf in fp16; a non-zero one below 2^-24 loses every significant bit (zero or the smallest
+// subnormal).  Values between 2^-24 and 2^-14 become fp16 subnormals, an absolute error below 2^-25,
+// and are not flagged; neither are Inf / NaN inputs, which are the caller's.
+__device__ __forceinline__ uint32_t bf16_range_bits(uint4v raw) {
+  uint32_t bits = 0u;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+#pragma unroll
+    for (int hlf = 0; hlf < 2; ++hlf) {
+      const uint32_t m = (hlf ? raw[k] >> 16 : raw[k]) & 0x7FFFu;
+      if (m >= 0x4780u && m < 0x7F80u) bits |= FTATTN_RANGE_OPERAND_OVERFLOW;
+      if (m != 0u && m < 0x3380u) bits |= FTATTN_RANGE_OPERAND_UNDERFLOW;
+    }
+  }
+  return bits;
+}
+
 // 8 consecutive 16-bit inputs (fp16 or bf16 patterns) -> fp16
 __device__ __forceinline__ half8 to_half8(uint4v raw, bool bf16) {
   if (!bf16) return __builtin_bit_cast(half8, raw);
@@ -153,12 +172,13 @@ __device__ __forceinline__ half8 to_half8(uint4v raw, bool bf16) {
 // check2[c,:] = sum_l (l+1) K[c+8l,:]  (eq. (13), (14)).
 template <int D>
 __device__ __forceinline__ void encode_k_tile(const void* __restrict__ k, int bf16, _Float16* __restrict__ kc,
-                                              int N, int Tj, int with_checksums, int j, int bh, int tid) {
+                                              int N, int Tj, int with_checksums, int j, int bh, int tid, uint32_t* range) {
   constexpr int KCH = D / 8;
   const int cls = tid / KCH, ch = tid % KCH;
   const uint16_t* src = reinterpret_cast<const uint16_t*>(k) + (size_t)bh * N * D + ch * 8;
   _Float16* out = kc + ((size_t)bh * Tj + j) * ((BN + CKR) * D) + ch * 8;
   float c1[8], c2[8];
+  uint32_t rbits = 0u;
 #pragma unroll
   for (int x = 0; x < 8; ++x) { c1[x] = 0.f; c2[x] = 0.f; }
 #pragma unroll
@@ -166,6 +186,7 @@ __device__ __forceinline__ void encode_k_tile(const void* __restrict__ k, int bf
     const int r = cls + 8 * l, key = j * BN + r;
     uint4v raw = (uint4v)0u;
     if (key < N) raw = *reinterpret_cast<const uint4v*>(src + (size_t)key * D);
+    if (bf16) rbits |= bf16_range_bits(raw);
     const half8 h = to_half8(raw, bf16 != 0);
     *reinterpret_cast<half8*>(out + r * D) = h;
 #pragma unroll
@@ -175,13 +196,19 @@ __device__ __forceinline__ void encode_k_tile(const void* __restrict__ k, int bf
       c2[x] += (float)(l + 1) * v;
     }
   }
-  if (!with_checksums) return;
+  if (!with_checksums) {
+    if (rbits) atomicOr(range, rbits);
+    return;
+  }
   half8 w0, w1, w2, w3;
 #pragma unroll
   for (int x = 0; x < 8; ++x) {
     w0[x] = (_Float16)c1[x]; w1[x] = (_Float16)(c1[x] - (float)w0[x]);
     w2[x] = (_Float16)c2[x]; w3[x] = (_Float16)(c2[x] - (float)w2[x]);
+    // a checksum beyond the fp16 range (the second one reaches 36 times the largest key value)
+    if ((finitef(c1[x]) && !finitef((float)w0[x])) || (finitef(c2[x]) && !finitef((float)w2[x]))) rbits |= FTATTN_RANGE_CHECKSUM_OVERFLOW;
   }
+  if (rbits) atomicOr(range, rbits);
   *reinterpret_cast<half8*>(out + (BN + cls) * D) = w0;
   *reinterpret_cast<half8*>(out + (BN + 8 + cls) * D) = w1;
   *reinterpret_cast<half8*>(out + (BN + 16 + cls) * D) = w2;
@@ -204,7 +231,8 @@ __device__ __forceinline__ int vt_key(int p) {
 // check1[key, c] = sum_l V[key, c+8l] and check2 with weights l+1.
 template <int D>
 __device__ __forceinline__ void encode_v_tile(const void* __restrict__ v, int bf16, _Float16* __restrict__ vt,
-                                              int N, int Tj, int with_checksums, int j, int bh, int tid) {
+                                              int N, int Tj, int with_checksums, int j, int bh, int tid, uint32_t* range) {
+  uint32_t rbits = 0u;
   // with_checksums == 2: class 0 also folds a column of ones at feature index D (fold D/8), which
   // makes the first checksum of class 0 carry the row-sum through GEMM II
   constexpr int KCH = D / 8, PITCH = D + 8;
@@ -216,6 +244,7 @@ __device__ __forceinline__ void encode_v_tile(const void* __restrict__ v, int bf
     const int r = e / KCH, ch = e % KCH, key = j * BN + r;
     uint4v raw = (uint4v)0u;
     if (key < N) raw = *reinterpret_cast<const uint4v*>(src + (size_t)key * D + ch * 8);
+    if (bf16) rbits |= bf16_range_bits(raw);
     *reinterpret_cast<half8*>(tile + r * PITCH + ch * 8) = to_half8(raw, bf16 != 0);
   }
   __syncthreads();
@@ -226,7 +255,10 @@ __device__ __forceinline__ void encode_v_tile(const void* __restrict__ v, int bf
     for (int x = 0; x < 8; ++x) h[x] = tile[vt_key(8 * pc + x) * PITCH + f];
     *reinterpret_cast<half8*>(out + f * BN + 8 * pc) = h;
   }
-  if (!with_checksums) return;
+  if (!with_checksums) {
+    if (rbits) atomicOr(range, rbits);
+    return;
+  }
   for (int e = tid; e < 8 * BN; e += 256) {
     const int cls = e / BN, kl = e % BN;
     float c1 = 0.f, c2 = 0.f;
@@ -238,6 +270,7 @@ __device__ __forceinline__ void encode_v_tile(const void* __restrict__ v, int bf
     }
     if (with_checksums == 2 && cls == 0 && j * BN + kl < N) { c1 += 1.0f; c2 += (float)(D / 8 + 1); }
     const _Float16 h1 = (_Float16)c1, h2 = (_Float16)c2;
+    if ((finitef(c1) && !finitef((float)h1)) || (finitef(c2) && !finitef((float)h2))) rbits |= FTATTN_RANGE_CHECKSUM_OVERFLOW;
     const int p = vt_pos(kl);
     cks[cls * BN + p] = h1;
     cks[(8 + cls) * BN + p] = (_Float16)(c1 - (float)h1);
@@ -246,6 +279,7 @@ __device__ __forceinline__ void encode_v_tile(const void* __restrict__ v, int bf
   }
   __syncthreads();
   *reinterpret_cast<half8*>(out + D * BN + tid * 8) = *reinterpret_cast<const half8*>(cks + tid * 8);
+  if (rbits) atomicOr(range, rbits);
 }
 
 // Everything the fused pass needs before it starts, in one launch (Algorithm 1: "Encode tensor
@@ -257,15 +291,18 @@ template <int D>
 __global__ __launch_bounds__(256) void ftattn_prepare(const void* __restrict__ k, const void* __restrict__ v, int bf16,
                                                       _Float16* __restrict__ kc, _Float16* __restrict__ vt, int N, int Tj,
                                                       int k_checksums, int v_checksums, int32_t* ev_count,
-                                                      unsigned long long* recheck, uint32_t* resmax, int n_resmax) {
+                                                      unsigned long long* recheck, uint32_t* resmax, int n_resmax,
+                                                      uint32_t* range, uint32_t* range_next) {
   const int j = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x;
   if (blockIdx.z == 0) {
     const long long i = ((long long)bh * Tj + j) * 256 + tid;
-    if (i == 0) { *ev_count = 0; *recheck = 0ull; }
+    // (the range word of THIS call is set by many workgroups of this launch, so it cannot be cleared
+    // here: each call clears the word the next call will use)
+    if (i == 0) { *ev_count = 0; *recheck = 0ull; *range_next = 0u; }
     if (i < n_resmax) resmax[i] = 0u;
-    encode_v_tile<D>(v, bf16, vt, N, Tj, v_checksums, j, bh, tid);
+    encode_v_tile<D>(v, bf16, vt, N, Tj, v_checksums, j, bh, tid, range);
   } else if (tid < D) {
-    encode_k_tile<D>(k, bf16, kc, N, Tj, k_checksums, j, bh, tid);
+    encode_k_tile<D>(k, bf16, kc, N, Tj, k_checksums, j, bh, tid, range);
   }
 }
 

@@ -192,12 +192,15 @@ __global__ __launch_bounds__(nwave_of(D) * 64, nwave_of(D) == 8 ? 1 : 2) void ft
   half8 qf[NSLAB];
   {
     const uint16_t* qp = reinterpret_cast<const uint16_t*>(a.q) + ((size_t)bh * N + (row < N ? row : 0)) * D + 8 * hi;
+    uint32_t qbits = 0u;
 #pragma unroll
     for (int sl = 0; sl < NSLAB; ++sl) {
       uint4v raw = *reinterpret_cast<const uint4v*>(qp + 16 * sl);
       if (row >= N) raw = (uint4v)0u;
+      if (a.q_bf16) qbits |= bf16_range_bits(raw);
       qf[sl] = to_half8(raw, a.q_bf16 != 0);
     }
+    if (qbits) atomicOr(a.range, qbits);
   }
 
   float16v o[NFB], oc, s[2], sc;

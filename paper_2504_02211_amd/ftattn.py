@@ -20,6 +20,7 @@ ST_S, ST_EXP, ST_ROWSUM, ST_OACC = 0, 1, 2, 3
 CHECK_S, CHECK_EXP, CHECK_L, CHECK_O = 0, 1, 2, 3
 FT_OFF, FT_CORRECT, FT_DETECT = 0, 1, 2
 OK, EINVAL, EUNSUPPORTED, EHIP, ENOMEM = 0, -1, -2, -3, -4
+RANGE_OPERAND_OVERFLOW, RANGE_OPERAND_UNDERFLOW, RANGE_CHECKSUM_OVERFLOW = 1, 2, 4
 
 EXPORTS = ("ftattn_create", "ftattn_get_config", "ftattn_forward", "ftattn_report", "ftattn_destroy",
            "ftattn_last_error", "ftattn_set_timing", "ftattn_get_timing", "ftattn_forward_static",
@@ -48,7 +49,7 @@ class ReportView(C.Structure):
     _fields_ = [("n_events", C.c_int32), ("n_events_dropped", C.c_int32), ("events", C.POINTER(Event)),
                 ("tiles_m", C.c_int32), ("tiles_n", C.c_int32), ("tile_flags", C.POINTER(C.c_uint8)),
                 ("rowtile_flags", C.POINTER(C.c_uint8)), ("residual_max", C.POINTER(C.c_float)),
-                ("recheck_entries", C.c_int64)]
+                ("recheck_entries", C.c_int64), ("range_flags", C.c_int32)]
 
 
 EVENT_DTYPE = np.dtype([("b", "<i4"), ("h", "<i4"), ("check", "<i4"), ("kv_tile", "<i4"), ("row", "<i4"),
@@ -119,6 +120,7 @@ class Report:
         self.residual_max = np.ctypeslib.as_array(view.residual_max, shape=(nrt * 4,)).copy().reshape(
             batch, heads, view.tiles_m, 4)
         self.recheck_entries = int(view.recheck_entries)
+        self.range_flags = int(view.range_flags)
 
     def event_set(self):
         """Set of (b, h, check, kv_tile, row, col) tuples."""

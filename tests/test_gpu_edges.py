@@ -237,3 +237,37 @@ def test_two_contexts_on_two_streams():
             assert torch.equal(o, r) and ctx.report().n_events == 0, rep
     for ctx in ctxs:
         ctx.close()
+
+
+def test_range_flags_report_operands_that_do_not_survive_the_conversion_to_fp16():
+    import torch
+    from paper_2504_02211_amd import ftattn
+    """bf16 inputs are converted to fp16 on entry: exact for 2^-14 <= |x| <= 65504, to 2^-25 below.  The report says
+    when an operand (Q, K or V) or a tensor checksum leaves that range; ordinary data raises nothing."""
+    shape = (1, 2, 200, 128)
+    q, k, v = synth.gen_qkv(shape, synth.BF16, 0xF1A6)
+    bf = lambda x: int(np.array([x], np.float32).view(np.uint32)[0] >> 16)
+    def flags(qq, kk, vv, dtype=synth.BF16):
+        _, rep, _ = H.run_gpu(qq, kk, vv, dtype, True)
+        return rep.range_flags
+    assert flags(q, k, v) == 0
+    k2 = k.copy(); k2[0, 1, 77, 5] = bf(1.0e5)              # becomes Inf in fp16
+    assert flags(q, k2, v) & ftattn.RANGE_OPERAND_OVERFLOW
+    v2 = v.copy(); v2[0, 0, 3, 100] = bf(1.0e-9)            # below 2^-24: nothing left of it in fp16
+    assert flags(q, k, v2) == ftattn.RANGE_OPERAND_UNDERFLOW
+    q2 = q.copy(); q2[0, 1, 199, 0] = bf(-7.0e4)
+    assert flags(q2, k, v) == ftattn.RANGE_OPERAND_OVERFLOW
+    k3 = k.copy(); k3[0, 0, 64:128, 9] = bf(3000.0)         # every key finite in fp16, the weighted checksum (36 x 3000) is not
+    assert flags(q, k3, v) == ftattn.RANGE_CHECKSUM_OVERFLOW
+    # a context reports each call on its own: a clean call after a flagged one reads 0
+    ctx = ftattn.FtAttn(*shape, synth.BF16, True)
+    o = torch.empty(shape, dtype=torch.float32, device="cuda")
+    for kk, want in ((k2, True), (k, False), (k, False), (k2, True)):
+        ctx.forward(H.to_torch(q, synth.BF16), H.to_torch(kk, synth.BF16), H.to_torch(v, synth.BF16), o)
+        assert bool(ctx.report().range_flags & ftattn.RANGE_OPERAND_OVERFLOW) == want
+    ctx.close()
+    # fp16 inputs need no conversion; their checksums can still overflow
+    qh, kh, vh = synth.gen_qkv(shape, synth.F16, 0xF1A7)
+    assert flags(qh, kh, vh, synth.F16) == 0
+    kh[0, 0, 0:64, 3] = int(np.array([3000.0], np.float16).view(np.uint16)[0])
+    assert flags(qh, kh, vh, synth.F16) == ftattn.RANGE_CHECKSUM_OVERFLOW
