@@ -92,6 +92,16 @@ listed in the design notes of the repository):
   and a row-sum that differs from its duplicate is reported (CHECK_L, with the key tile) and
   replaced by the duplicate.  The product-form check and the range restriction are not used.
 
+* ``rescale_margin`` (an extension, off by default; Algorithm 1 renews the maximum in every iteration
+  and rescales the output with it).  The subtracted value is a *reference* maximum m_ref that is
+  replaced by the running maximum only when that exceeds it by more than the margin; in all other
+  iterations the rescale factor is exactly one and the rescale of O, of its checksums, of the
+  row-sum and of its lower bound falls away.  Exponentials then lie in (0, e^margin] instead of
+  (0, 1]; every identity of the method holds with m_ref in place of the maximum (Section 3.4,
+  case 1: the subtracted value cancels between numerator and denominator), and the upper bound of
+  the row-sum becomes (number of unmasked keys) * exp(running maximum - m_ref).  Not combined with
+  the other variants.
+
 Thresholds (eps1, tau_o, delta_l) are this repository's choices: the paper's own
 values (0.48 absolute, 7e-6 relative) belong to its one-word fp16 checksums and
 carry a 5.9% false-alarm rate.  Which faults the paper's code would flag at a
@@ -123,6 +133,8 @@ class Params:
                                        # checksum class 0 and is verified / repaired exactly (see below)
     per_step: bool = False             # True: verification after every step instead of unified (see above)
     softmax_dmr: bool = False          # True (needs per_step): softmax protected by duplication, not by SNVR
+    rescale_margin: float = 0.0        # > 0 (an extension, see above): the reference maximum is renewed only when the
+                                       # running maximum exceeds it by more than this (natural-log units)
 
 
 def bitflip32(x: float, bit: int) -> float:
@@ -417,7 +429,7 @@ def efta_rows(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: np.ndarray,
               ) -> Tuple[np.ndarray, List[Event], Dict[str, float]]:
     """Algorithm 1 for query rows ``row_idx`` of one head: ``efta_rows_unified`` (the paper's method),
     or, when ``prm`` asks for one of the verification variants, ``efta_rows_with_modes``."""
-    if prm.rowsum_fold or prm.per_step or prm.softmax_dmr:
+    if prm.rowsum_fold or prm.per_step or prm.softmax_dmr or prm.rescale_margin > 0:
         return efta_rows_with_modes(Q, row_idx, K, V, prm, faults, max_shift)
     return efta_rows_unified(Q, row_idx, K, V, prm, faults, max_shift)
 
@@ -469,6 +481,10 @@ def efta_rows_with_modes(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: n
     l_step_distance = np.inf   # per_step: smallest relative distance of a row-sum to its range, any iteration
     assert not (prm.per_step and prm.rowsum_fold)
     assert prm.per_step or not prm.softmax_dmr
+    lazy = prm.rescale_margin > 0
+    assert not (lazy and (prm.per_step or prm.rowsum_fold))
+    m_true = np.full(n, -np.inf)   # running maximum (with rescale_margin, m holds the reference maximum)
+    n_rescales = 0                 # (row, iteration) pairs with a rescale factor other than one
     n_tiles = (N + Bc - 1) // Bc
 
     for j in range(n_tiles):
@@ -501,16 +517,20 @@ def efta_rows_with_modes(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: n
                 flipped.append((ST_S, float(S[loc[ri], col - k0])))
                 S[loc[ri], col - k0] = bitflip32(S[loc[ri], col - k0], bit)
 
-        def softmax_part(Srows, vrows, m_old):
+        def softmax_part(Srows, vrows, m_old, mt_old=None):
             with np.errstate(all="ignore"):
                 mh = np.where(vrows, sc * Srows, -np.inf).max(axis=1)
-                mn = np.maximum(m_old, mh)
+                if lazy:
+                    mt = np.maximum(mt_old, mh)
+                    mn = np.where(mt > m_old + prm.rescale_margin, mt, m_old)     # renewed only beyond the margin
+                else:
+                    mn = np.maximum(m_old, mh)
                 x = sc * Srows - mn[:, None]
                 P = np.where(vrows, np.exp(x), 0.0)
             return mh, mn, x, P
 
         # reduce max, element-wise exp
-        m_hat, m_new, x, P = softmax_part(S, valid, m[act])
+        m_hat, m_new, x, P = softmax_part(S, valid, m[act], m_true[act])
         for (jt, row), dm in (max_shift or {}).items():
             if jt == j and int(row) in pos and pos[int(row)] in loc:
                 i = loc[pos[int(row)]]
@@ -576,12 +596,14 @@ def efta_rows_with_modes(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: n
                         if prm.correct:
                             P[i, cols[l]] = good[l]
         for i in sorted(set(redo)):
-            mh, mn, xx, PP = softmax_part(S[i:i + 1], valid[i:i + 1], m[act[i]:act[i] + 1])
+            mh, mn, xx, PP = softmax_part(S[i:i + 1], valid[i:i + 1], m[act[i]:act[i] + 1], m_true[act[i]:act[i] + 1])
             m_hat[i], m_new[i], x[i], P[i] = mh[0], mn[0], xx[0], PP[0]
+        m_true[act] = np.maximum(m_true[act], m_hat)
 
         # reduce sum, GEMM II with rescale
         with np.errstate(all="ignore"):
             alpha = np.exp(m[act] - m_new)
+            n_rescales += int(np.count_nonzero(np.isfinite(m[act]) & (alpha != 1.0)))
             ell[act] = alpha * ell[act] + P.sum(axis=1)
             lower[act] = alpha * lower[act] + np.where(np.isfinite(m_hat), np.exp(m_hat - m_new), 0.0)
             ell_dup = ell.copy()               # the second evaluation of the reduce-sum (softmax_dmr)
@@ -638,6 +660,9 @@ def efta_rows_with_modes(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: n
                     Ot[r, cols[lstar]] = val
 
     U = np.minimum(row_idx + 1, N).astype(np.float64) if prm.causal else np.full(n, float(N))
+    if lazy:
+        with np.errstate(all="ignore"):
+            U = U * np.exp(m_true - m)         # exponentials reach exp(running maximum - reference maximum)
     l_ratio = 0.0
     if prm.rowsum_fold:
         # exact check of the row-sum against the one the class-0 checksum implies
@@ -698,7 +723,8 @@ def efta_rows_with_modes(Q: np.ndarray, row_idx: np.ndarray, K: np.ndarray, V: n
             O[i, cols[lstar]] = val
     diag = {"lambda_ratio": float(lam_ratio), "o_ratio": float(o_ratio),
             "l_distance": float(dist.min()) if n else np.inf, "l_ratio": float(l_ratio), "flipped": flipped,
-            "lin_ratio": float(lin_ratio), "o_step_ratio": float(o_step_ratio), "l_step_distance": float(l_step_distance)}
+            "lin_ratio": float(lin_ratio), "o_step_ratio": float(o_step_ratio), "l_step_distance": float(l_step_distance),
+            "rescales": n_rescales}
     return O, sorted(events), diag
 
 

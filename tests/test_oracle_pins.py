@@ -677,3 +677,71 @@ def test_unified_path_and_the_variant_function_take_the_same_steps():
                 assert np.array_equal(a[0], b[0], equal_nan=True)
                 for key in ("lambda_ratio", "o_ratio", "l_distance", "flipped"):
                     assert a[2][key] == b[2][key] or (a[2][key] != a[2][key] and b[2][key] != b[2][key]), key
+
+
+# ---------------------------------------------------------------- lazily renewed reference maximum (rescale_margin)
+
+def test_rescale_margin_leaves_the_result_alone_and_saves_rescales():
+    """The subtracted value cancels between numerator and denominator (Section 3.4, case 1), so a
+    reference maximum that lags behind the running one by at most the margin gives the definition's
+    result, silently, with far fewer iterations whose rescale factor differs from one."""
+    rng = np.random.default_rng(91)
+    for (N, d, Bc, causal) in ((300, 16, 32, True), (257, 8, 64, False), (96, 24, 16, True)):
+        Q, K, V = (rng.standard_normal((N, d)) * 1.5 for _ in range(3))
+        ref = attention_clean(Q, K, V, 0.5, causal)
+        counts = []
+        for margin in (1e-9, 0.7, 3.0, 5.5):
+            prm = orc.Params(scale=0.5, causal=causal, block_n=Bc, rescale_margin=margin)
+            O, ev, dg = efta_rows(Q, np.arange(N), K, V, prm)
+            assert ev == [] and np.abs(O - ref).max() < 1e-12
+            counts.append(dg["rescales"])
+        assert counts[0] > 2 * max(1, counts[2]) and counts[0] > 4 * max(1, counts[3]) and counts == sorted(counts, reverse=True)
+
+
+def test_rescale_margin_row_sum_range_uses_the_lagging_reference():
+    """With a lagging reference the exponentials reach exp(running maximum - reference), and so does
+    the row-sum per key: the upper bound carries that factor (a row built to exceed the plain key
+    count stays silent), the lower bound is unchanged, and a flipped row-sum is still replaced by the
+    lower bound with the closed form O_ft = O_clean * l_true / L."""
+    d, Bc = 8, 16
+    N = 4 * Bc
+    K = np.zeros((N, d)); K[:, 0] = 1.0
+    K[Bc:, 0] = 1.9                       # every later key scores 0.9 above the first tile's, within the margin
+    Q = np.zeros((1, d)); Q[0, 0] = 1.0
+    V = np.random.default_rng(5).standard_normal((N, d))
+    prm = orc.Params(scale=1.0, causal=False, block_n=Bc, rescale_margin=1.0)
+    O, ev, dg = efta_rows(Q, np.array([0]), K, V, prm)
+    ell = Bc + 3 * Bc * np.exp(0.9)        # relative to the reference (the first tile's maximum)
+    assert ell > N and ev == [] and dg["rescales"] == 0
+    assert np.abs(O - attention_clean(Q, K, V, 1.0, False)).max() < 1e-13
+    # the same row under Algorithm 1 proper: the maximum moves once, the row-sum is below the key count
+    _, ev0, _ = efta_rows(Q, np.array([0]), K, V, orc.Params(scale=1.0, causal=False, block_n=Bc))
+    assert ev0 == []
+    # a row-sum flipped far out of range is replaced by the lower bound L = sum of exp(tile maximum - reference)
+    O2, ev2, _ = efta_rows(Q, np.array([0]), K, V, prm, [(ST_ROWSUM, 3, 0, 0, 30)])
+    assert ev2 == [(CHECK_L, -1, 0, 0)]
+    L = 1.0 + 3 * np.exp(0.9)
+    assert np.abs(O2 - attention_clean(Q, K, V, 1.0, False) * ell / L).max() < 1e-12
+
+
+def test_rescale_margin_faults_are_found_where_algorithm_1_finds_them():
+    rng = np.random.default_rng(92)
+    N, d, Bc = 128, 16, 32
+    Q, K, V = (rng.standard_normal((N, d)) for _ in range(3))
+    base = orc.Params(scale=0.4, causal=True, block_n=Bc)
+    lazy = orc.Params(scale=0.4, causal=True, block_n=Bc, rescale_margin=4.0)
+    ref = attention_clean(Q, K, V, 0.4, True)
+    faults, rows = [], set()
+    while len(faults) < 24:
+        st = (ST_S, ST_EXP, ST_OACC)[len(faults) % 3]
+        row = int(rng.integers(8, N))
+        if row in rows:
+            continue
+        rows.add(row)
+        kt = int(rng.integers(0, row // Bc + 1))
+        col = int(rng.integers(kt * Bc, min(row, kt * Bc + Bc - 1) + 1)) if st != ST_OACC else int(rng.integers(0, d))
+        faults.append((st, kt, row, col, int(rng.integers(26, 31))))
+    O0, ev0, _ = efta_rows(Q, np.arange(N), K, V, base, faults)
+    O1, ev1, _ = efta_rows(Q, np.arange(N), K, V, lazy, faults)
+    assert ev0 == ev1 and len(ev0) >= 20
+    assert np.abs(O1 - ref).max() < 1e-9 and np.abs(O0 - ref).max() < 1e-9
