@@ -110,7 +110,7 @@ def stats(xs):
     return {"median": round(x[len(x) // 2], 4), "min": round(x[0], 4), "mean": round(sum(x) / len(x), 4), "n": len(x)}
 
 
-def time_pair(torch, ftattn, w, tq, tk, tv, steps, warmup, block_m, rowsum_fold=False, per_step=0, stride=8):
+def time_pair(torch, ftattn, w, tq, tk, tv, steps, warmup, block_m, rowsum_fold=False, per_step=0, stride=8, rescale_margin=0.0):
     """Times the protected pass and its twin with every check compiled out.
 
     (1) `steps` protected steps back to back between two synchronisations: the step time the metric
@@ -122,8 +122,8 @@ def time_pair(torch, ftattn, w, tq, tk, tv, steps, warmup, block_m, rowsum_fold=
     shape = (w.batch, w.heads, w.seq, w.head_dim)
     o = torch.empty(shape, dtype=torch.float32, device="cuda")
     mk = lambda mode, **kw: ftattn.FtAttn(w.batch, w.heads, w.seq, w.head_dim, w.dtype, w.causal, ft_mode=mode, block_m=block_m, **kw)
-    ft = mk(ftattn.FT_CORRECT, rowsum_fold=rowsum_fold, per_step=per_step, stride=stride)
-    un = mk(ftattn.FT_OFF)
+    ft = mk(ftattn.FT_CORRECT, rowsum_fold=rowsum_fold, per_step=per_step, stride=stride, rescale_margin=rescale_margin)
+    un = mk(ftattn.FT_OFF, rescale_margin=rescale_margin)
     stream = torch.cuda.Stream()
     sp = stream.cuda_stream
     for _ in range(max(10, warmup)):
@@ -344,6 +344,9 @@ def main():
     ap.add_argument("--stride", type=int, choices=(8, 1), default=8,
                     help="attention: checksum stride; 1 = the traditional checksum (one class per tile row) the paper "
                          "compares its stride-8 tensor checksum with")
+    ap.add_argument("--rescale-margin", type=float, default=0.0,
+                    help="attention: renew the subtracted maximum only when the running maximum exceeds it by this margin "
+                         "(natural-log units; an extension, both variants); 0 = Algorithm 1 as printed")
     ap.add_argument("--decoupled", action="store_true",
                     help="time the decoupled three-kernel scheme of the paper's Section 3.1 against the fused kernel (its own JSON line)")
     ap.add_argument("--linear", action="store_true",
@@ -378,7 +381,7 @@ def main():
         w = synth.WORKLOADS[cfg]
         q, k, v = synth.gen_workload(cfg)
         tq, tk, tv = (to_dev(x, w.dtype) for x in (q, k, v))
-        results[cfg] = (w,) + time_pair(torch, ftattn, w, tq, tk, tv, args.steps, args.warmup, args.block_m, args.rowsum_fold, args.per_step, args.stride)
+        results[cfg] = (w,) + time_pair(torch, ftattn, w, tq, tk, tv, args.steps, args.warmup, args.block_m, args.rowsum_fold, args.per_step, args.stride, args.rescale_margin)
         if cfg == args.workload:
             keep = (q, k, v)
         del tq, tk, tv
@@ -389,7 +392,7 @@ def main():
     tf = fl / (ft["ms_step"] * 1e-3) / 1e12
     tf_un = fl / (un["ms_step"] * 1e-3) / 1e12
     tf_kernel = fl / (ft["main"]["mean"] * 1e-3) / 1e12
-    default_mode = not (args.rowsum_fold or args.per_step or args.stride != 8 or args.block_m)
+    default_mode = not (args.rowsum_fold or args.per_step or args.stride != 8 or args.block_m or args.rescale_margin > 0)
     traffic, traffic_note = profile_traffic(f"ftattn_main_cfg{w.cfg}_{w.name.replace(' ', '_').replace('-', '_')}_hbm_traffic.txt") if default_mode else (None, "non-default mode")
     out = {
         "metric": "FT-attention TFLOP/s at 1 GPU, % overhead vs unprotected, % MFMA peak",
@@ -400,7 +403,8 @@ def main():
                                f"{'bf16' if w.dtype else 'fp16'} in, fp32 out, {'causal' if w.causal else 'non-causal'}, fault-free",
                    "block_m": ft["block_m"], "block_n": ft["block_n"], "stride": args.stride,
                    "rowsum_protection": "extra checksum fold" if args.rowsum_fold else "range restriction",
-                   "verification": ("unified", "after every step", "after every step, duplicated softmax")[args.per_step]},
+                   "verification": ("unified", "after every step", "after every step, duplicated softmax")[args.per_step],
+                   "reference_maximum": f"renewed beyond a margin of {args.rescale_margin}" if args.rescale_margin > 0 else "renewed in every iteration (Algorithm 1)"},
         "unprotected_tflops": round(tf_un, 2), "unprotected_ms_per_step": round(un["ms_step"], 4),
         # overhead of the whole step (encode + fused kernel) from the interleaved per-launch medians;
         # the back-to-back figure next to it is the ratio of the two K-step means

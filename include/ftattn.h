@@ -118,6 +118,14 @@ typedef struct {
                              (FTATTN_CHECK_EXP) and replaced, a differing row-sum likewise
                              (FTATTN_CHECK_L with its key tile).
                              1 and 2 need ft_mode FTATTN_FT_CORRECT and rowsum_fold 0. */
+  float rescale_margin;   /* <= 0: Algorithm 1 as printed (the maximum is renewed in every iteration).
+                             > 0 (an extension, at most 8): the subtracted value is a reference maximum
+                             that is replaced by the running maximum only when that exceeds it by more
+                             than this margin (natural-log units); otherwise the rescale factor is one
+                             and the rescale of the output, of its checksums and of the row-sum is
+                             skipped.  Exponentials reach e^margin instead of 1; the upper bound of the
+                             row-sum range carries exp(running maximum - reference).  Applies to the
+                             unprotected variant too.  Needs per_step 0, stride 8, rowsum_fold 0. */
   int32_t max_events;     /* capacity of the event log; <= 0 selects 65536 */
   int32_t device;         /* HIP device ordinal */
 } ftattn_config;

@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "libftattn.so")
 SOURCES = [os.path.join(PKG, "csrc", "ftattn.hip"), os.path.join(PKG, "csrc", "ftattn_perstep.hip"),
-           os.path.join(PKG, "csrc", "ftattn_elementwide.hip"),
+           os.path.join(PKG, "csrc", "ftattn_elementwide.hip"), os.path.join(PKG, "csrc", "ftattn_lazy.hip"),
            os.path.join(PKG, "csrc", "ftgemm.hip"), os.path.join(PKG, "csrc", "ftdecoupled.hip")]
 HEADERS = [os.path.join(PKG, "csrc", "ftattn_device.h"), os.path.join(PKG, "csrc", "ftattn_main.h"),
            os.path.join(PKG, "csrc", "ftgemm_main.h"), os.path.join(ROOT, "include", "ftattn.h"),

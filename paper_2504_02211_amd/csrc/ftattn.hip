@@ -102,6 +102,7 @@ static main_fn pick(bool ft, bool causal) {
 namespace ftattn {
 void (*select_perstep(int D, bool causal, bool inject, int mode))(const KArgs);
 void (*select_elementwide(int D, bool causal, bool inject))(const KArgs);
+void (*select_lazy(int D, bool ft, bool causal, bool inject))(const KArgs);
 }
 
 static main_fn select_kernel(int D, bool ft, bool causal, bool inject) {
@@ -143,7 +144,13 @@ static int resolve_config(const ftattn_config* cfg, ftattn_config& e, Geometry& 
     why = "stride 1 needs a protected ft_mode, rowsum_fold 0 and per_step 0";
     return FTATTN_EINVAL;
   }
+  if (cfg->rescale_margin > 0.f && (cfg->per_step != 0 || cfg->stride == 1 || cfg->rowsum_fold != 0)) {
+    why = "rescale_margin needs per_step 0, stride 8 and rowsum_fold 0";
+    return FTATTN_EINVAL;
+  }
+  if (cfg->rescale_margin > 8.f) { why = "rescale_margin must be at most 8 (the exponentials are held in fp16)"; return FTATTN_EINVAL; }
   e = *cfg;
+  if (!(e.rescale_margin > 0.f)) e.rescale_margin = 0.f;
   e.stride = cfg->stride == 1 ? 1 : 8;
   e.block_n = BN;
   if (!(e.softmax_scale > 0.f)) e.softmax_scale = 1.0f / std::sqrt((float)e.head_dim);
@@ -162,13 +169,20 @@ static int resolve_config(const ftattn_config* cfg, ftattn_config& e, Geometry& 
 }
 
 // Lets the kernels of one head size (and mode) use their dynamic LDS.  Needs the device current.
-static hipError_t allow_lds(int D, int per_step, int stride, const char*& why) {
+static hipError_t allow_lds(int D, int per_step, int stride, const char*& why, bool lazy = false) {
   why = "no kernel for this tile shape";
   for (int v = 0; v < 8; ++v) {
     const int ft = v & 1, ca = (v >> 1) & 1;
     main_fn f = select_kernel(D, ft != 0, ca != 0, (v >> 2) != 0);
     if (!f) return hipErrorInvalidValue;
     hipError_t he = hipFuncSetAttribute((const void*)f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes(D, ft != 0));
+    if (he != hipSuccess) { why = "hipFuncSetAttribute"; return he; }
+  }
+  for (int v = 0; v < 8 && lazy; ++v) {
+    const bool ft = (v & 1) != 0;
+    main_fn f = select_lazy(D, ft, (v & 2) != 0, (v & 4) != 0);
+    if (!f) return hipErrorInvalidValue;
+    hipError_t he = hipFuncSetAttribute((const void*)f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes(D, ft));
     if (he != hipSuccess) { why = "hipFuncSetAttribute"; return he; }
   }
   for (int v = 0; v < 4 && (per_step || stride == 1); ++v) {
@@ -227,7 +241,7 @@ extern "C" int ftattn_create(const ftattn_config* cfg, ftattn_ctx** out) {
   CREATE_TRY(hipMemset(c->d_recheck, 0, sizeof(unsigned long long)));
   CREATE_TRY(hipMemset(c->d_resmax, 0, sizeof(uint32_t) * n_rt * 4));
   {
-    hipError_t le = allow_lds(e.head_dim, e.per_step, e.stride, why);
+    hipError_t le = allow_lds(e.head_dim, e.per_step, e.stride, why, e.rescale_margin > 0.f);
     if (le != hipSuccess) {
       int rc = fail(nullptr, le == hipErrorInvalidValue ? FTATTN_EUNSUPPORTED : FTATTN_EHIP, std::string(why) + ": " + hipGetErrorString(le));
       release(c);
@@ -274,12 +288,14 @@ static hipError_t launch_pass(const ftattn_config& e, const Geometry& g, const B
   a.tau_o = e.tau_o; a.delta_l = e.delta_l;
   a.correct = e.ft_mode == FTATTN_FT_CORRECT ? 1 : 0;
   a.rowsum_fold = e.rowsum_fold;
+  a.rescale_margin = e.rescale_margin;
   a.faults = b.faults;
   a.fault_off = inject ? b.fault_off : nullptr;
   a.events = b.events; a.ev_count = b.ev_count; a.max_events = e.max_events;
   a.resmax = b.resmax; a.recheck = b.recheck; a.range = b.range;
   main_fn f = e.per_step ? select_perstep(D, e.causal != 0, inject, e.per_step)
               : e.stride == 1 ? select_elementwide(D, e.causal != 0, inject)
+              : e.rescale_margin > 0.f ? select_lazy(D, ft, e.causal != 0, inject)
                               : select_kernel(D, ft, e.causal != 0, inject);
   if (timing && (he = hipEventRecord(timing[1], st)) != hipSuccess) return he;
   hipLaunchKernelGGL(f, dim3(g.BH * g.Ti), dim3(nwave_of(D) * 64), lds_bytes(D, ft), st, a);
@@ -464,7 +480,8 @@ extern "C" int ftattn_forward_static(const ftattn_config* cfg, const void* q, co
   Geometry g;
   const char* why;
   if (int rc = resolve_config(cfg, e, g, why)) return static_fail(rc, why);
-  if (e.per_step != 0 || e.stride != 8) return static_fail(FTATTN_EUNSUPPORTED, "the static entry point runs the default verification scheme (per_step 0, stride 8)");
+  if (e.per_step != 0 || e.stride != 8 || e.rescale_margin > 0.f)
+    return static_fail(FTATTN_EUNSUPPORTED, "the static entry point runs the default verification scheme (per_step 0, stride 8, rescale_margin 0)");
   if (e.device < 0 || e.device >= STATIC_MAX_DEVICES) return static_fail(FTATTN_EINVAL, "device ordinal out of range");
   if (!q || !k || !v || !o) return static_fail(FTATTN_EINVAL, "null tensor pointer");
   if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o) & 15) return static_fail(FTATTN_EINVAL, "tensor pointers must be 16-byte aligned");

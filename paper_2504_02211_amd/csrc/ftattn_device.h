@@ -54,6 +54,7 @@ struct KArgs {
   float eps1, tau_fast, tau_o, delta_l;
   int32_t correct;         // 1: repair, 0: detect only
   int32_t rowsum_fold;     // 1: the row-sum is an extra fold of checksum class 0 of the value tiles
+  float rescale_margin;    // (lazy mode) the reference maximum is renewed beyond this, natural-log units
   const DevFault* faults;  // sorted by (bh, row tile, kv_tile)
   const int32_t* fault_off;  // [BH*Ti + 1] or nullptr
   ftattn_event* events;

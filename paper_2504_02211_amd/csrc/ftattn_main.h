@@ -86,10 +86,15 @@ __device__ __forceinline__ half2v opaque(half2v x) { asm volatile("" : "+v"(x));
 // the two lanes of a query together, and can name one element of 64 (of D for the output).
 template <int D, bool FT, bool CAUSAL, bool INJ, int PS = 0>
 __global__ __launch_bounds__(nwave_of(D) * 64, nwave_of(D) == 8 ? 1 : 2) void ftattn_main(const KArgs a) {
-  static_assert(FT || PS == 0, "the verification modes are modes of the protected kernel");
+  static_assert(FT || PS == 0 || PS == 4, "the verification modes are modes of the protected kernel");
   constexpr bool DMR = PS == 2;
   constexpr bool STEP = PS == 1 || PS == 2;
   constexpr bool EW = PS == 3;
+  // PS == 4 (an extension): the subtracted maximum is a reference that is renewed only when the running
+  // maximum exceeds it by more than a margin; in all other iterations the rescale factor is exactly
+  // one and the rescale of the output falls away.  Exponentials then reach e^margin; every identity of
+  // Algorithm 1 holds with the reference in place of the maximum (Section 3.4, case 1).
+  constexpr bool LAZY = PS == 4;
   using U = Unit<D, FT>;
   constexpr int NWAVE = U::NWAVE, BM = NWAVE * 32, NSTAGE = U::NSTAGE;
   constexpr bool ALT = NWAVE == 8;      // two wave groups alternating between the phases (else: free-running waves)
@@ -214,6 +219,13 @@ __global__ __launch_bounds__(nwave_of(D) * 64, nwave_of(D) == 8 ? 1 : 2) void ft
   for (int fb = 0; fb < NFB; ++fb) o[fb] = (float16v)0.f;
   oc = (float16v)0.f;
   float m_run = -__builtin_inff(), l_part = 0.f, l_low = 0.f, dev_max = 0.f;
+  float m_true = -__builtin_inff();       // (LAZY) the running maximum; m_run is then the reference
+  // the maximum to subtract after a key tile whose maximum is mxv (Algorithm 1: m_ij = max(m_i,j-1, rowmax))
+  auto renewed = [&](const float mxv) __attribute__((always_inline)) -> float {
+    if (!LAZY) return fmax2(m_run, mxv);
+    const float mt = fmax2(m_true, mxv);
+    return (mt - m_run) * a.scale > a.rescale_margin ? mt : m_run;      // (a reference of -inf is always renewed)
+  };
   unsigned rechecks = 0;
 
   // The matrix phase as one stream of (LDS operand read, MFMA) pairs: first GEMM II of a key tile,
@@ -498,7 +510,7 @@ __global__ __launch_bounds__(nwave_of(D) * 64, nwave_of(D) == 8 ? 1 : 2) void ft
           m1 = fmax2(fmax2(m1, s[1][v]), s[1][v + 1]);
         }
         mx = max32(fmax2(m0, m1));
-        m_new = fmax2(m_run, mx);
+        m_new = renewed(mx);
         negm = -m_new * sl2;
         // all 32 arguments first, then all 32 exponentials, in place: neighbouring instructions are
         // independent, where (argument, exponential) pairs through one temporary would each wait
@@ -524,7 +536,7 @@ __global__ __launch_bounds__(nwave_of(D) * 64, nwave_of(D) == 8 ? 1 : 2) void ft
             mx = fmax2(mx, ok ? s[kb][v] : -__builtin_inff());
           }
         mx = max32(mx);
-        m_new = fmax2(m_run, mx);
+        m_new = renewed(mx);
         negm = -m_new * sl2;
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
@@ -579,7 +591,7 @@ __global__ __launch_bounds__(nwave_of(D) * 64, nwave_of(D) == 8 ? 1 : 2) void ft
                 for (int v = 0; v < 16; ++v) mc = fmax2(mc, s[kb][v]);
               mc = max32(mc);
               if (as_u(mc) == as_u(mxb)) mx = mxb;          // two of three agree on the duplicate
-              m_new = fmax2(m_run, mx);
+              m_new = renewed(mx);
               negm = -m_new * sl2;
               bad = true;                                    // every exponential is looked at again below
             }
@@ -823,7 +835,7 @@ __global__ __launch_bounds__(nwave_of(D) * 64, nwave_of(D) == 8 ? 1 : 2) void ft
             mx2 = max32(mx2);
             if (redo) {
               mx = mx2;
-              m_new = fmax2(m_run, mx);
+              m_new = renewed(mx);
               negm = -m_new * sl2;
             }
 #pragma unroll
@@ -841,7 +853,11 @@ __global__ __launch_bounds__(nwave_of(D) * 64, nwave_of(D) == 8 ? 1 : 2) void ft
 
       // ============ rescale factor, lower bound of the row-sum (carried with the same rescale as the
       // row-sum itself, which is completed in the matrix phase), first quarter of P in fp16
-      al = ex2(__builtin_fmaf(m_run, sl2, negm));
+      if (LAZY) m_true = fmax2(m_true, mx);
+      // e^{m_old - m_new}, formed from the difference so that an unchanged maximum gives exactly one (the
+      // product m_old * sl2 against the rounded m_new * sl2 would leave a rounding residue, and with it a
+      // rescale of the whole output by 1 + 2^-23)
+      al = ex2((m_run - m_new) * sl2);
       if (FT) l_low = l_low * al + ex2(__builtin_fmaf(mx, sl2, negm));
       m_run = m_new;
       convert_quarter(0);
@@ -1009,6 +1025,7 @@ __global__ __launch_bounds__(nwave_of(D) * 64, nwave_of(D) == 8 ? 1 : 2) void ft
     }
     if (FT && !lfold && !DMR) {
       float Ub = CAUSAL ? (float)(row + 1 < N ? row + 1 : N) : (float)N;
+      if (LAZY) Ub *= ex2((m_true - m_run) * sl2);      // exponentials reach exp(running maximum - reference)
       float lo = l_low;
       bool detl = real && !(lo * (1.f - a.delta_l) <= l && l <= Ub * (1.f + a.delta_l));
       if (!detl && real) { rmax_u = fmax2(rmax_u, l / Ub); rmax_l = fmax2(rmax_l, lo / l); }

@@ -33,7 +33,8 @@ class Config(C.Structure):
                 ("head_dim", C.c_int32), ("in_dtype", C.c_int32), ("out_dtype", C.c_int32), ("causal", C.c_int32),
                 ("softmax_scale", C.c_float), ("ft_mode", C.c_int32), ("stride", C.c_int32), ("block_m", C.c_int32),
                 ("block_n", C.c_int32), ("eps1", C.c_float), ("tau_o", C.c_float), ("delta_l", C.c_float),
-                ("rowsum_fold", C.c_int32), ("per_step", C.c_int32), ("max_events", C.c_int32), ("device", C.c_int32)]
+                ("rowsum_fold", C.c_int32), ("per_step", C.c_int32), ("rescale_margin", C.c_float), ("max_events", C.c_int32),
+                ("device", C.c_int32)]
 
 
 class Fault(C.Structure):
@@ -163,7 +164,7 @@ def forward_static(q, k, v, o, batch: int, heads: int, seq: int, head_dim: int, 
     number of events, or None."""
     lib = load_library()
     cfg = Config(C.sizeof(Config), batch, heads, seq, head_dim, in_dtype, out_dtype, int(bool(causal)), softmax_scale,
-                 ft_mode, 8, 0, 0, 0.0, 0.0, 0.0, int(bool(rowsum_fold)), 0, 0, device)
+                 ft_mode, 8, 0, 0, 0.0, 0.0, 0.0, int(bool(rowsum_fold)), 0, 0.0, 0, device)
     n = batch * heads * seq * head_dim
     ptr = lambda t, name, dt: C.c_void_p(None) if t is None else device_pointer(t, name, n, dt, device)
     nev = C.c_void_p(None) if n_events is None else C.c_void_p(n_events if isinstance(n_events, int) else n_events.data_ptr())
@@ -179,10 +180,11 @@ class FtAttn:
     def __init__(self, batch: int, heads: int, seq: int, head_dim: int, in_dtype: int, causal: bool,
                  out_dtype: int = F32, ft_mode: int = FT_CORRECT, softmax_scale: float = 0.0, block_m: int = 0,
                  eps1: float = 0.0, tau_o: float = 0.0, delta_l: float = 0.0, max_events: int = 0, device: int = 0,
-                 rowsum_fold: bool = False, per_step: int = 0, stride: int = 8):
+                 rowsum_fold: bool = False, per_step: int = 0, stride: int = 8, rescale_margin: float = 0.0):
         self.lib = load_library()
         cfg = Config(C.sizeof(Config), batch, heads, seq, head_dim, in_dtype, out_dtype, int(bool(causal)),
-                     softmax_scale, ft_mode, int(stride), block_m, 0, eps1, tau_o, delta_l, int(bool(rowsum_fold)), int(per_step), max_events, device)
+                     softmax_scale, ft_mode, int(stride), block_m, 0, eps1, tau_o, delta_l, int(bool(rowsum_fold)), int(per_step),
+                     float(rescale_margin), max_events, device)
         self.handle = C.c_void_p()
         rc = self.lib.ftattn_create(C.byref(cfg), C.byref(self.handle))
         if rc != OK:

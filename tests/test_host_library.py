@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_layouts_match_header():
-    assert C.sizeof(ftattn.Config) == 20 * 4
+    assert C.sizeof(ftattn.Config) == 21 * 4
     assert C.sizeof(ftattn.Fault) == 7 * 4
     assert C.sizeof(ftattn.Event) == 8 * 4 == ftattn.EVENT_DTYPE.itemsize
 
@@ -40,7 +40,7 @@ def test_create_rejects_bad_configs_without_a_device():
     def create(**kw):
         base = dict(struct_size=C.sizeof(ftattn.Config), batch=1, heads=1, seq=128, head_dim=64, in_dtype=0, out_dtype=2,
                     causal=0, softmax_scale=0.0, ft_mode=1, stride=8, block_m=0, block_n=0, eps1=0.0, tau_o=0.0,
-                    delta_l=0.0, rowsum_fold=0, per_step=0, max_events=0, device=0)
+                    delta_l=0.0, rowsum_fold=0, per_step=0, rescale_margin=0.0, max_events=0, device=0)
         base.update(kw)
         cfg = ftattn.Config(**base)
         h = C.c_void_p()
@@ -63,6 +63,10 @@ def test_create_rejects_bad_configs_without_a_device():
     assert create(stride=1, ft_mode=0)[0] == ftattn.EINVAL           # the traditional checksum is a mode of the protected kernel
     assert create(stride=1, rowsum_fold=1)[0] == ftattn.EINVAL
     assert create(stride=1, per_step=1)[0] == ftattn.EINVAL
+    assert create(rescale_margin=2.0, per_step=1)[0] == ftattn.EINVAL      # the lazily renewed maximum is a mode of the unified scheme
+    assert create(rescale_margin=2.0, rowsum_fold=1)[0] == ftattn.EINVAL
+    assert create(rescale_margin=2.0, stride=1)[0] == ftattn.EINVAL
+    assert create(rescale_margin=9.0)[0] == ftattn.EINVAL                  # exponentials beyond the fp16 range
     rc, msg = create(block_m=96)
     assert rc == ftattn.EUNSUPPORTED and "block_m" in msg
     assert create(block_m=256)[0] == ftattn.EUNSUPPORTED       # head_dim 64 runs 128-query row tiles
