@@ -128,3 +128,35 @@ def test_decoupled_rejects_bad_faults_and_long_rows_run_from_memory():
     ref = eorc.attention_clean(Q[rows], K, V, float(cfg.softmax_scale), True, rows)
     ma, rf = H.tolerance_ok(out[0, 0][rows], ref)
     assert ma <= MAX_ABS and rf <= REL_FRO
+
+
+def test_decoupled_random_shapes_and_unprotected_damage():
+    """Seeded random shapes (ragged lengths, both head sizes and types, masks) without faults; then one
+    exponent-bit fault per stage with the checks off: no event, and the damage is in the output."""
+    rng = np.random.default_rng(0xDEC9)
+    for it in range(8):
+        B, Hh, N = int(rng.integers(1, 3)), int(rng.integers(1, 3)), int(rng.integers(1, 500))
+        d, dtype, causal = int(rng.choice([64, 128])), int(rng.integers(0, 2)), bool(rng.integers(0, 2))
+        print(f"[decoupled random] B{B} H{Hh} N{N} d{d} dtype{dtype} causal{causal}", flush=True)
+        q, k, v = synth.gen_qkv((B, Hh, N, d), dtype, 0xDECA + it)
+        out, rep, cfg, _ = _run(q, k, v, dtype, causal)
+        assert rep.n_events == 0
+        for b in range(B):
+            for h in range(Hh):
+                Q, K, V = (H.head_f64(x, dtype, b, h) for x in (q, k, v))
+                ma, rf = H.tolerance_ok(out[b, h], eorc.attention_clean(Q, K, V, float(cfg.softmax_scale), causal))
+                assert ma <= MAX_ABS and rf <= REL_FRO, (it, b, h, ma, rf)
+    shape = (1, 1, 192, 64)
+    q, k, v = synth.gen_qkv(shape, synth.F16, 0xDECB)
+    clean, _, _, _ = _run(q, k, v, synth.F16, True, ft_mode=ftdecoupled.FT_OFF)
+    for f in ([0, 0, 0, 100, 40, 29], [0, 0, 1, 101, 7, 29], [0, 0, 3, 102, 5, 29]):
+        bad, rep, _, _ = _run(q, k, v, synth.F16, True, np.array([f], np.int32), ft_mode=ftdecoupled.FT_OFF)
+        assert rep.n_events == 0
+        row = f[3]
+        assert not np.isfinite(bad[0, 0, row]).all() or np.abs(bad[0, 0, row] - clean[0, 0, row]).max() > 2e-3, f
+        others = np.arange(192) != row
+        # (the injecting variant of the softmax kernel rounds P to fp16 in two steps where the plain one
+        # fuses multiply and conversion: other rows agree to the last fp16 digit of a weight, not bit for bit)
+        assert np.abs(bad[0, 0][others] - clean[0, 0][others]).max() <= 1e-4
+        fixed, rep, _, _ = _run(q, k, v, synth.F16, True, np.array([f], np.int32))
+        assert rep.n_events == 1 and np.abs(fixed[0, 0] - clean[0, 0]).max() <= 1e-4, f

@@ -26,12 +26,15 @@ def test_random_attention_configurations(seed):
         fold = bool(rng.integers(0, 2)) and mode == 0
         stride = 1 if mode == 0 and not fold and bool(rng.integers(0, 2)) else 8      # 1: the traditional checksum
         scale = float(rng.choice([1.0, 0.25, 2.0]))
-        tag = f"B{B} H{Hh} N{N} d{d} dtype{dtype} causal{causal} rowsum_fold{fold} per_step{mode} stride{stride} scale{scale}"
+        # (drawn from a generator of its own so that the configurations of earlier versions of this test stay as they were)
+        margin = float(np.random.default_rng(31 * seed + it).choice([0.0, 0.0, 0.7, 4.0])) if mode == 0 and not fold and stride == 8 else 0.0
+        tag = f"B{B} H{Hh} N{N} d{d} dtype{dtype} causal{causal} rowsum_fold{fold} per_step{mode} stride{stride} scale{scale} margin{margin}"
         print(f"[random attention] {tag}", flush=True)
         q, k, v = synth.gen_qkv((B, Hh, N, d), dtype, 1000 * seed + it, value_scale=scale)
-        out, rep, c = H.run_gpu(q, k, v, dtype, causal, rowsum_fold=fold, per_step=mode, stride=stride)
+        out, rep, c = H.run_gpu(q, k, v, dtype, causal, rowsum_fold=fold, per_step=mode, stride=stride, rescale_margin=margin)
         prm = H.oracle_params(N, d, causal, block_n=c.block_n, scale=c.softmax_scale, eps1=c.eps1, tau_o=c.tau_o,
-                              delta_l=c.delta_l, rowsum_fold=fold, per_step=mode > 0, softmax_dmr=mode == 2, stride=stride)
+                              delta_l=c.delta_l, rowsum_fold=fold, per_step=mode > 0, softmax_dmr=mode == 2, stride=stride,
+                              rescale_margin=float(c.rescale_margin))
         assert rep.n_events == 0, (tag, rep.events[:4])
         rows = np.unique(rng.integers(0, N, size=min(N, 24)))
         for b in range(B):
@@ -50,7 +53,7 @@ def test_random_attention_configurations(seed):
             continue
         skipped += redraws
         accepted += len(faults)
-        out2, rep2, _ = H.run_gpu(q, k, v, dtype, causal, faults, rowsum_fold=fold, per_step=mode, stride=stride)
+        out2, rep2, _ = H.run_gpu(q, k, v, dtype, causal, faults, rowsum_fold=fold, per_step=mode, stride=stride, rescale_margin=margin)
         expected, got, ref = set(), [], []
         for (b, h) in sorted({(int(f[0]), int(f[1])) for f in faults}):
             fr = np.array(sorted({int(f[4]) for f in faults if f[0] == b and f[1] == h}))
