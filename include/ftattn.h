@@ -166,7 +166,9 @@ typedef struct {
                                  contractions run on fp16 MFMA for either input type, and a bf16 operand
                                  of magnitude >= 65536 or < 2^-24, or a checksum beyond 65504, does not survive the conversion.
                                  The pass still runs (results follow IEEE arithmetic on the converted values);
-                                 the caller decides whether to rescale its inputs. */
+                                 the caller decides whether to rescale its inputs.  Each forward call reports
+                                 on its own; replays of one captured graph share a flag word, so after
+                                 replays the bits are those of any replay since the capture. */
 } ftattn_report_view;
 
 /* Validates cfg, allocates all device scratch for this shape on cfg->device. */
