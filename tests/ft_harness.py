@@ -24,8 +24,9 @@ def select_faults(slots, seed: int, q, k, v, dtype: int, prm: orc.Params, bit_lo
                   max_attempts: int = 200) -> Tuple[np.ndarray, int]:
     """Draws one fault per slot from the seeded candidate streams, skipping candidates whose
     detection would hinge on rounding (oracle statistics within 4x of a threshold), whose flipped
-    value sits on a binade edge or (row-sum) has an uncertain value of the flipped mantissa bit, that
-    break the one-fault-per-cycle rule, or that share a row with an accepted fault.  Returns (int32
+    value sits on a binade edge or (row-sum) has an uncertain value of the flipped mantissa bit, whose
+    substituted row-sum blows the output row up (more than twofold, beyond +-2), that break the one-fault-per-cycle rule, or
+    that share a row with an accepted fault.  Returns (int32
     [n,7] fault array, number of skipped candidates); callers bound the skipped share with
     ``assert_skip_share``."""
     B, H, N, d = q.shape
@@ -44,8 +45,16 @@ def select_faults(slots, seed: int, q, k, v, dtype: int, prm: orc.Params, bit_lo
             if synth.conflicts(f, accepted) or any(g[0] == b and g[1] == h and g[4] == row for g in accepted):
                 redraws += 1
                 continue
-            _, _, dg = orc.efta_rows(Q[row:row + 1], np.array([row]), K, V, prm, [f[2:]])
+            o_ft, ev, dg = orc.efta_rows(Q[row:row + 1], np.array([row]), K, V, prm, [f[2:]])
             ok = orc.fault_is_robust(dg) and len(dg["flipped"]) == 1 and not orc.fp32_is_fragile(dg["flipped"][0][1], f[2], f[6])
+            # A row-sum replaced by its lower bound (the paper's approximate repair) multiplies the whole output row
+            # by l_true / L, and with it the kernel's rounding error (fp16 weights: up to 1e-3 of the output): blown
+            # up by more than 2x to beyond +-2, that error alone can pass the absolute bar of 2e-3, so such a
+            # candidate decides nothing.
+            if ok and any(e[0] == orc.CHECK_L for e in ev) and np.isfinite(o_ft).all() and np.abs(o_ft).max() > 2.0:
+                clean = orc.attention_clean(Q[row:row + 1], K, V, prm.scale, prm.causal, np.array([row]))
+                if np.abs(o_ft).max() > 2.0 * np.abs(clean).max():
+                    ok = False
             if ok:
                 accepted.append(f)
                 break
