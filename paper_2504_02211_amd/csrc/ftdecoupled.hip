@@ -140,7 +140,9 @@ __global__ __launch_bounds__(256) void ftdec_softmax(const SArgs a) {
     const float inv = 1.0f / l;
     // ---- normalised weights; eq. (12)
     float psum = 0.f;
-    for (int j = tid; j < a.Np; j += 256) {
+    // (causal: GEMM II stops at the last query of the row's 256-query tile; the weights beyond are never read)
+    const int jend = a.causal && (row / 256 + 1) * 256 < a.Np ? (row / 256 + 1) * 256 : a.Np;
+    for (int j = tid; j < jend; j += 256) {
       float p = 0.f;
       if (j < nvalid) {
         const float s = src[j];
@@ -416,6 +418,8 @@ extern "C" int ftdec_forward(ftdec_ctx* c, const void* q, const void* k, const v
     a.M = N; a.N = N; a.K = d; a.Tm = c->Tm; a.Tn = c->Tn1;
     if (!n_g) {
       a.bs_x = a.bs_w = (long long)N * d; a.bs_wc = wc1_stride; a.bs_y_bytes = (long long)N * N * 4; a.bs_events = (long long)cap;
+      a.skip_upper = e.causal;      // score tiles above the diagonal are never read by the softmax (with a fault
+                                    // list the matrix is computed in full: a fault may name any score)
     }
     DHIP_TRY(c, ftgemm::gemm_launch(a, ft, a.n_faults > 0, bf, st, n_g ? 1 : BH));
   }
@@ -451,6 +455,7 @@ extern "C" int ftdec_forward(ftdec_ctx* c, const void* q, const void* k, const v
     if (!n_g) {
       a.bs_x = (long long)N * Np; a.bs_w = (long long)d * Np; a.bs_wc = wc2_stride; a.bs_y_bytes = (long long)N * d * 4;
       a.bs_events = (long long)cap;
+      a.k_lower = e.causal;         // P is lower-triangular: keys beyond a tile's last query contribute nothing
     }
     DHIP_TRY(c, ftgemm::gemm_launch(a, ft, a.n_faults > 0, false, st, n_g ? 1 : BH));
   }

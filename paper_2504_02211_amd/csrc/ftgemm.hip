@@ -215,6 +215,7 @@ extern "C" int ftgemm_forward(ftgemm_ctx* c, const void* x, const void* w, void*
   a.M = tr ? e.n : e.m; a.N = tr ? e.m : e.n; a.K = e.k; a.Tm = c->Tm; a.Tn = c->Tn;
   a.transposed = tr ? 1 : 0;
   a.bs_x = a.bs_w = a.bs_wc = a.bs_y_bytes = a.bs_events = 0;
+  a.skip_upper = 0; a.k_lower = 0;
   a.tau_rel = e.tau_rel; a.tau_abs = e.tau_abs;
   a.correct = e.ft_mode == FTGEMM_FT_CORRECT ? 1 : 0;
   a.faults = c->d_faults; a.n_faults = n_faults;

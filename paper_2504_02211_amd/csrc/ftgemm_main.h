@@ -76,6 +76,10 @@ struct GArgs {
   // wc and the event log, byte stride of y; counters and residual maxima are one per problem.  All
   // zero for a single product.
   long long bs_x, bs_w, bs_wc, bs_y_bytes, bs_events;
+  int32_t skip_upper;      // 1: output tiles that lie entirely above the diagonal (first feature > last token) are
+                           // not computed and not written (the score matrix of a causal attention: nobody reads them)
+  int32_t k_lower;         // 1: x is lower-triangular (the weights of a causal attention): contraction steps beyond the
+                           // last token of the tile multiply zeros and are skipped
   int32_t transposed;      // 1: the kernel's (token, feature) is the caller's (column, row) of Y: checksums over the
                            // caller's token rows; results are stored, and events named, with the two exchanged
 };
@@ -186,6 +190,7 @@ __global__ __launch_bounds__(GWAVES * 64) void ftgemm_main(const GArgs a0) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int M = a.M, N = a.N, K = a.K;
   const int m0 = tm * GBM, n0 = tn * GBN;
+  if (a.skip_upper && n0 > m0 + GBM - 1) return;      // (the whole workgroup, before any barrier)
   const int nkb = (K + GBK - 1) / GBK;
   const int krem = K - (nkb - 1) * GBK;     // columns of the last K step (GBK unless K is ragged; K is a multiple of 8)
   const uint32_t smem_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)smem;
@@ -238,11 +243,13 @@ __global__ __launch_bounds__(GWAVES * 64) void ftgemm_main(const GArgs a0) {
 #pragma unroll
   for (int i = 0; i < S::NLOAD; ++i) issue_piece(i, 0, 0, true);
 
-  for (int kb = 0; kb < nkb; ++kb) {
+  int nkb_run = nkb;                       // (the ragged-K handling below stays keyed to the full count)
+  if (a.k_lower) { const int lim = (m0 + GBM + GBK - 1) / GBK; nkb_run = lim < nkb ? lim : nkb; }
+  for (int kb = 0; kb < nkb_run; ++kb) {
     const int st = kb & 1;
     wait_vmcnt<0>();                       // this wave's pieces of stage st have landed
     phase_barrier();                       // ... everyone's; and everyone is done reading the other stage
-    const bool more = kb + 1 < nkb;
+    const bool more = kb + 1 < nkb_run;
     const char* wst = wrow + st * S::BYTES;
     const char* xst = xrow + st * S::BYTES;
     half8 xf[NKS];
